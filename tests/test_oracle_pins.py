@@ -1,0 +1,406 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Each test names the passage it leans on.  None of them re-types the oracle's
+formula and compares it with itself: the expected values come from closed forms,
+library routines (numpy SVD / QR / dense matrix products) or invariants.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import pg_oracle as O
+from paper_2008_01425_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def ring(n):
+    return W.ring_edges(n)
+
+
+def make(n, edges, w, shapes, rank=1, steps=1):
+    ew = np.full(len(edges), w) if np.isscalar(w) else np.asarray(w, dtype=np.float64)
+    return O.Problem(n, np.asarray(edges), ew, shapes, rank, steps)
+
+
+def rand_state(prob, rng, dtype=np.float64, sigma=0.3):
+    bases = [rng.standard_normal(s) for s in prob.shapes]
+    X = [[(b + sigma * rng.standard_normal(b.shape)).astype(dtype) for b in bases]
+         for _ in range(prob.n_workers)]
+    Q = [[rng.standard_normal((prob.layer_rank(l), prob.shapes[l][1])).astype(dtype)
+          for l in range(len(prob.shapes))] for _ in range(prob.n_edges)]
+    return X, Q
+
+
+def copy_state(X, Q):
+    return [[a.copy() for a in r] for r in X], [[a.copy() for a in r] for r in Q]
+
+
+def consensus_distance(X):
+    n = len(X)
+    tot = 0.0
+    for l in range(len(X[0])):
+        mean = sum(X[i][l].astype(np.float64) for i in range(n)) / n
+        tot += sum(((X[i][l].astype(np.float64) - mean) ** 2).sum() for i in range(n))
+    return tot / n
+
+
+# ---------------------------------------------------------------- Lemma 1
+@pytest.mark.parametrize("dtype,tol", [(np.float64, 1e-13), (np.float32, 2e-6)])
+@pytest.mark.parametrize("topo", ["ring5", "torus3x3", "star"])
+def test_average_is_preserved(dtype, tol, topo):
+    """Lemma 1 (appendix, 'Preserves average'): the worker mean never moves."""
+    rng = np.random.default_rng(1)
+    if topo == "ring5":
+        n, edges, w = 5, ring(5), 1 / 3
+    elif topo == "torus3x3":
+        n, edges, w = 9, W.torus_edges(3, 3), 1 / 5
+    else:
+        n, edges, w = 4, np.array([[0, 1], [2, 0], [0, 3]]), 0.25
+    prob = make(n, edges, w, [(12, 7), (5, 9), (6, 1)], rank=2, steps=2)
+    X, Q = rand_state(prob, rng, dtype)
+    before = [sum(X[i][l].astype(np.float64) for i in range(n)) for l in range(3)]
+    for _ in range(3):
+        O.gossip_round(prob, X, Q)
+    for l in range(3):
+        after = sum(X[i][l].astype(np.float64) for i in range(n))
+        assert np.abs(after - before[l]).max() <= tol * np.abs(before[l]).max()
+
+
+# ------------------------------------------------- best rank-1 (Section 3)
+def test_exact_rank_one_difference_is_recovered_in_one_step():
+    """Section 3: with v the top right singular vector, C_v(D) is the best rank-1
+    approximation; a difference that IS rank 1 is therefore reproduced exactly after
+    one power step from any start not orthogonal to it, and w = 1/2 lands both
+    workers on their mean."""
+    rng = np.random.default_rng(2)
+    p, q = 9, 6
+    u, v = rng.standard_normal(p), rng.standard_normal(q)
+    base = rng.standard_normal((p, q))
+    Xa, Xb = base + 0.5 * np.outer(u, v), base - 0.5 * np.outer(u, v)
+    prob = make(2, [[0, 1]], 0.5, [(p, q)])
+    X, Q = [[Xa.copy()], [Xb.copy()]], [[rng.standard_normal((1, q))]]
+    info = O.gossip_round(prob, X, Q, want_phat=True)
+    ph = info.phat[0][0][0]
+    sgn = np.sign(ph @ u)
+    assert np.allclose(ph, sgn * u / np.linalg.norm(u), atol=1e-12)
+    # Q' = D^T Phat = +-||u|| v
+    assert np.allclose(Q[0][0][0], sgn * np.linalg.norm(u) * v, atol=1e-12)
+    assert np.allclose(X[0][0], base, atol=1e-12)
+    assert np.allclose(X[1][0], base, atol=1e-12)
+
+
+# ------------------------------------------- Eq. (3): power iteration -> SVD
+@pytest.mark.parametrize("rank", [1, 2, 3])
+def test_frozen_parameters_converge_to_top_singular_triplets(rank):
+    """Eq. (3): when the difference does not change, the scheme is power iteration.
+    With zero edge weight X is frozen; many warm-started rounds must reach the top-r
+    left singular vectors (columns of Phat) and Q'_k = sigma_k * right singular vector."""
+    rng = np.random.default_rng(3)
+    p, q = 14, 10
+    U, _ = np.linalg.qr(rng.standard_normal((p, p)))
+    V, _ = np.linalg.qr(rng.standard_normal((q, q)))
+    sv = np.array([5.0, 3.0, 1.5, 0.4, 0.3, 0.2, 0.1, 0.05, 0.02, 0.01])
+    D = (U[:, :q] * sv) @ V.T
+    base = rng.standard_normal((p, q))
+    prob = make(2, [[0, 1]], 0.0, [(p, q)], rank=rank)
+    X, Q = [[base + D], [base.copy()]], [[rng.standard_normal((rank, q))]]
+    D = X[0][0] - X[1][0]
+    Us, ss, Vts = np.linalg.svd(D)
+    for _ in range(60):
+        info = O.gossip_round(prob, X, Q, want_phat=True)
+    assert np.array_equal(X[0][0] - X[1][0], D)          # w = 0: nothing moved
+    ph = info.phat[0][0]
+    for k in range(rank):
+        s = np.sign(ph[k] @ Us[:, k])
+        assert np.allclose(ph[k], s * Us[:, k], atol=1e-8)
+        assert np.allclose(Q[0][0][k], s * ss[k] * Vts[k], atol=1e-8)
+        assert abs(np.linalg.norm(Q[0][0][k]) - ss[k]) < 1e-9
+
+
+def test_subspace_error_shrinks_at_power_iteration_rate():
+    """Eq. (3) again, quantitatively: the angle to the top left singular vector shrinks
+    by about (sigma_2/sigma_1)^2 per power step (one step = two of the paper's iterations)."""
+    rng = np.random.default_rng(4)
+    p, q = 12, 8
+    U, _ = np.linalg.qr(rng.standard_normal((p, p)))
+    V, _ = np.linalg.qr(rng.standard_normal((q, q)))
+    sv = np.array([2.0, 1.0, 0.1, 0.05, 0.02, 0.01, 0.005, 0.001])
+    D = (U[:, :q] * sv) @ V.T
+    prob = make(2, [[0, 1]], 0.0, [(p, q)])
+    X, Q = [[D.copy()], [np.zeros((p, q))]], [[rng.standard_normal((1, q))]]
+    Us = np.linalg.svd(D)[0]
+    errs = []
+    for _ in range(8):
+        info = O.gossip_round(prob, X, Q, want_phat=True)
+        ph = info.phat[0][0][0]
+        errs.append(np.sqrt(max(0.0, 1 - (ph @ Us[:, 0]) ** 2)))
+    ratios = np.array(errs[2:7]) / np.array(errs[1:6])
+    assert np.all(ratios < 0.27) and np.all(ratios > 0.23)   # (1/2)^2 = 0.25
+
+
+# ------------------------------------------------ Theorem 1 / Lemma 2 step
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_consensus_distance_never_increases_on_tiny_ring(dtype):
+    """Theorem 1 bounds the expected contraction; with projections Pi <= I (the step used in
+    Lemma 2) the round is x <- (I - M) x with 0 <= M <= (I - W) (x) I <= 2I, so the distance
+    to the mean cannot grow in any single round.  Checked on the 4-worker ring workload."""
+    wl = W.get("tiny")
+    prob = O.Problem(wl.n_workers, wl.edges, wl.edge_w.astype(np.float64), wl.shapes, 1, 1)
+    X = [[a.astype(dtype) for a in row] for row in wl.all_params()]
+    Q = [[a.astype(dtype) for a in row] for row in wl.all_q()]
+    prev = consensus_distance(X)
+    first = prev
+    for _ in range(wl.rounds):
+        O.gossip_round(prob, X, Q)
+        cur = consensus_distance(X)
+        assert cur <= prev * (1 + 1e-12)
+        prev = cur
+    assert prev < 0.7 * first
+
+
+# --------------------------------------------- Eq. (1): uncompressed gossip
+@pytest.mark.parametrize("steps", [1, 2])
+def test_full_rank_reduces_to_plain_gossip(steps):
+    """Eq. (1) without the gradient: when r >= p <= q the projector Phat Phat^T is the
+    identity and a round is the textbook X <- W X over workers."""
+    rng = np.random.default_rng(5)
+    n, p, q = 6, 4, 9
+    edges = ring(n)
+    w = 0.3
+    prob = make(n, edges, w, [(p, q)], rank=p, steps=steps)
+    X, Q = rand_state(prob, rng)
+    Wm = np.zeros((n, n))
+    for a, b in edges:
+        Wm[a, b] = Wm[b, a] = w
+    Wm += np.diag(1 - Wm.sum(1))
+    stacked = np.stack([X[i][0] for i in range(n)])               # (n, p, q)
+    expect = np.einsum("ij,jpq->ipq", Wm, stacked)
+    O.gossip_round(prob, X, Q)
+    got = np.stack([X[i][0] for i in range(n)])
+    assert np.allclose(got, expect, atol=1e-12)
+
+
+def test_vectors_follow_exact_gossip_whatever_the_rank():
+    """The parameter tables list bias vectors with compression 'None': a p x 1 layer has
+    r_l = 1 and the rank-1 projection of a vector is the vector itself."""
+    rng = np.random.default_rng(6)
+    n = 5
+    edges = ring(n)
+    w = 1 / 3
+    prob = make(n, edges, w, [(11, 1)], rank=3, steps=1)
+    X, Q = rand_state(prob, rng)
+    Wm = np.zeros((n, n))
+    for a, b in edges:
+        Wm[a, b] = Wm[b, a] = w
+    Wm += np.diag(1 - Wm.sum(1))
+    expect = np.einsum("ij,jpq->ipq", Wm, np.stack([X[i][0] for i in range(n)]))
+    O.gossip_round(prob, X, Q)
+    assert np.allclose(np.stack([X[i][0] for i in range(n)]), expect, atol=1e-13)
+
+
+# --------------------------------------------------- Section 3.1 fixed point
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_consensus_is_a_fixed_point(dtype):
+    """Section 3.1: if two workers agree, the compressed update is zero.  Identical workers
+    stay bit-identical, the projection vectors are kept, nothing becomes NaN."""
+    rng = np.random.default_rng(7)
+    prob = make(4, ring(4), 1 / 3, [(8, 5), (3, 1)], rank=2)
+    base = [rng.standard_normal(s).astype(dtype) for s in prob.shapes]
+    X = [[b.copy() for b in base] for _ in range(4)]
+    Q = [[rng.standard_normal((prob.layer_rank(l), prob.shapes[l][1])).astype(dtype)
+          for l in range(2)] for _ in range(4)]
+    Q0 = [[a.copy() for a in r] for r in Q]
+    info = O.gossip_round(prob, X, Q, want_phat=True)
+    for i in range(4):
+        for l in range(2):
+            assert np.array_equal(X[i][l], base[l])
+    for e in range(4):
+        for l in range(2):
+            assert np.array_equal(Q[e][l], Q0[e][l])
+            assert not np.any(info.phat[e][l])
+    assert all(d.all() for d in info.degenerate)
+
+
+# --------------------------- assumption A5: the applied operator is a projection
+@pytest.mark.parametrize("rank", [1, 3])
+def test_applied_update_is_the_left_projection_of_the_difference(rank):
+    """Section 4.1 (left projection L(X) = v v^T X, rank-k form) and Eq. (2): the correction a
+    round applies on an edge is w * Phat Phat^T (X_a - X_b), subtracted from a and added to b;
+    Phat is orthonormal and equals the QR factor of D Q (library QR, signs fixed)."""
+    rng = np.random.default_rng(8)
+    p, q, w = 10, 7, 0.4
+    prob = make(2, [[0, 1]], w, [(p, q)], rank=rank)
+    X, Q = rand_state(prob, rng)
+    Xa, Xb, Q0 = X[0][0].copy(), X[1][0].copy(), Q[0][0].copy()
+    D = Xa - Xb
+    info = O.gossip_round(prob, X, Q, want_phat=True)
+    ph = info.phat[0][0]                                    # (r, p)
+    assert np.allclose(ph @ ph.T, np.eye(rank), atol=1e-13)
+    Qf, Rf = np.linalg.qr(D @ Q0.T)                        # p x r
+    Qf = Qf * np.sign(np.diag(Rf))
+    assert np.allclose(ph.T, Qf, atol=1e-11)
+    proj = ph.T @ ph                                        # p x p projector
+    assert np.allclose(X[0][0], Xa - w * proj @ D, atol=1e-13)
+    assert np.allclose(X[1][0], Xb + w * proj @ D, atol=1e-13)
+    assert np.allclose(Q[0][0], (D.T @ ph.T).T, atol=1e-13)
+    # idempotent and contractive (A5: C(C(X)) = C(X); Pi <= I)
+    assert np.allclose(proj @ proj, proj, atol=1e-12)
+    assert np.linalg.norm(D - proj @ D) <= np.linalg.norm(D) * (1 + 1e-14)
+
+
+def test_compressor_is_linear_in_the_difference():
+    """A5, first identity, for a frozen projection: C(D1 + D2) = C(D1) + C(D2).  With the same
+    Phat (same D Q direction) the update is linear in w and in D; checked by scaling D."""
+    rng = np.random.default_rng(9)
+    p, q = 6, 5
+    base = rng.standard_normal((p, q))
+    D = rng.standard_normal((p, q))
+    outs = []
+    for scale in (1.0, 2.0):
+        prob = make(2, [[0, 1]], 0.25, [(p, q)])
+        X = [[base + scale * D], [base.copy()]]
+        Q = [[np.ones((1, q))]]
+        O.gossip_round(prob, X, Q)
+        outs.append(X[1][0] - base)
+    assert np.allclose(outs[1], 2.0 * outs[0], atol=1e-13)
+
+
+# ------------------------------------------------ Algorithm 2: v_ij = -v_ji
+def test_reversing_an_edge_negates_its_state_and_leaves_parameters_alone():
+    """Algorithm 2, line 1 and the closing note: v_ij = -v_ji and C(X_j - X_i) = -C(X_i - X_j).
+    Seen from the other endpoint an edge has the negated difference and the negated vector:
+    the same Phat, the negated Q', the same parameters.  Keeping the vector and negating only
+    the difference negates Phat instead and leaves Q' alone."""
+    rng = np.random.default_rng(10)
+    shapes = [(7, 5), (4, 6)]
+    prob_f = make(3, [[0, 1], [1, 2], [2, 0]], 1 / 3, shapes, rank=2, steps=2)
+    prob_r = make(3, [[0, 1], [2, 1], [2, 0]], 1 / 3, shapes, rank=2, steps=2)
+    X, Q = rand_state(prob_f, rng)
+    X2, Q2 = copy_state(X, Q)
+    X3, Q3 = copy_state(X, Q)
+    Q2[1] = [-a for a in Q2[1]]
+    i1 = O.gossip_round(prob_f, X, Q, want_phat=True)
+    i2 = O.gossip_round(prob_r, X2, Q2, want_phat=True)
+    i3 = O.gossip_round(prob_r, X3, Q3, want_phat=True)
+    for i in range(3):
+        for l in range(2):
+            assert np.allclose(X[i][l], X2[i][l], atol=1e-14)
+            assert np.allclose(X[i][l], X3[i][l], atol=1e-14)
+    for l in range(2):
+        assert np.allclose(Q[1][l], -Q2[1][l], atol=1e-14)
+        assert np.allclose(i1.phat[1][l], i2.phat[1][l], atol=1e-14)
+        assert np.allclose(Q[1][l], Q3[1][l], atol=1e-14)
+        assert np.allclose(i1.phat[1][l], -i3.phat[1][l], atol=1e-14)
+        assert np.allclose(Q[0][l], Q2[0][l], atol=1e-14)
+
+
+def test_relabelling_workers_permutes_the_result():
+    rng = np.random.default_rng(11)
+    n = 5
+    prob = make(n, ring(n), 1 / 3, [(6, 4)], rank=1)
+    X, Q = rand_state(prob, rng)
+    perm = np.array([2, 3, 4, 0, 1])                       # rotation: a ring automorphism
+    X2 = [[X[perm[i]][0].copy()] for i in range(n)]
+    Q2 = [[Q[(e + 2) % n][0].copy()] for e in range(n)]
+    O.gossip_round(prob, X, Q)
+    O.gossip_round(prob, X2, Q2)
+    for i in range(n):
+        assert np.allclose(X2[i][0], X[perm[i]][0], atol=1e-14)
+
+
+# ------------------------------------------------ Algorithm 2: s power steps
+def test_extra_power_steps_run_on_frozen_parameters_and_apply_only_the_last():
+    """Algorithm 2 takes the difference as a fixed argument, overwrites its approximation in
+    the loop and returns it once: s = 2 equals one step with zero weight (state advances,
+    parameters frozen) followed by one step with the real weight."""
+    rng = np.random.default_rng(12)
+    shapes = [(9, 6)]
+    X, Q = rand_state(make(4, ring(4), 1 / 3, shapes, rank=2), rng)
+    Xs, Qs = copy_state(X, Q)
+    O.gossip_round(make(4, ring(4), 1 / 3, shapes, rank=2, steps=2), X, Q)
+    O.gossip_round(make(4, ring(4), 0.0, shapes, rank=2, steps=1), Xs, Qs)
+    O.gossip_round(make(4, ring(4), 1 / 3, shapes, rank=2, steps=1), Xs, Qs)
+    for i in range(4):
+        assert np.array_equal(X[i][0], Xs[i][0])
+    for e in range(4):
+        assert np.array_equal(Q[e][0], Qs[e][0])
+
+
+def test_all_edges_read_start_of_round_parameters():
+    """Eq. (2) / Eq. (4) put time t-1 on the whole right-hand side: on a path 0-1-2 the update
+    of worker 1 is the sum of the two single-edge corrections computed from the old values."""
+    rng = np.random.default_rng(13)
+    shapes = [(5, 4)]
+    X, Q = rand_state(make(3, [[0, 1], [1, 2]], 0.3, shapes), rng)
+    Xa, Qa = copy_state(X, Q)
+    Xb, Qb = copy_state(X, Q)
+    O.gossip_round(make(3, [[0, 1], [1, 2]], 0.3, shapes), X, Q)
+    O.gossip_round(make(3, [[0, 1]], 0.3, shapes), Xa, [Qa[0]])
+    O.gossip_round(make(3, [[1, 2]], 0.3, shapes), Xb, [Qb[1]])
+    start = copy_state(rand_state(make(3, [[0, 1], [1, 2]], 0.3, shapes),
+                                  np.random.default_rng(13))[0], [])[0]
+    for i in range(3):
+        both = (Xa[i][0] - start[i][0]) + (Xb[i][0] - start[i][0])
+        assert np.allclose(X[i][0] - start[i][0], both, atol=1e-14)
+
+
+# ------------------------------------------------------- degenerate columns
+def test_rank_deficient_difference_flags_the_extra_column():
+    """Section 3.1's zero-difference rule extended to columns: a rank-1 difference compressed at
+    rank 2 has a vanishing second Gram-Schmidt residual; that column is dropped (zero Phat,
+    projection vector kept) and the first column still recovers the difference."""
+    rng = np.random.default_rng(14)
+    p, q = 8, 6
+    u, v = rng.standard_normal(p), rng.standard_normal(q)
+    base = rng.standard_normal((p, q))
+    prob = make(2, [[0, 1]], 0.5, [(p, q)], rank=2)
+    X = [[base + np.outer(u, v)], [base.copy()]]
+    Q0 = rng.standard_normal((2, q))
+    Q = [[Q0.copy()]]
+    info = O.gossip_round(prob, X, Q, want_phat=True)
+    assert info.degenerate[0].tolist() == [[0, 1]]
+    assert not np.any(info.phat[0][0][1])
+    assert np.array_equal(Q[0][0][1], Q0[1])
+    assert np.allclose(X[0][0], base + 0.5 * np.outer(u, v), atol=1e-12)
+    assert np.allclose(X[1][0], base + 0.5 * np.outer(u, v), atol=1e-12)
+
+
+# ----------------------------------------------------------- precision
+def test_float_storage_tracks_the_all_double_oracle():
+    """The float-storage build differs from the all-double build only by storage rounding."""
+    wl = W.get("tiny")
+    prob = O.Problem(wl.n_workers, wl.edges, wl.edge_w.astype(np.float64), wl.shapes, 1, 1)
+    X32, Q32 = wl.all_params(), wl.all_q()
+    X64 = [[a.astype(np.float64) for a in r] for r in X32]
+    Q64 = [[a.astype(np.float64) for a in r] for r in Q32]
+    O.gossip_round(prob, X32, Q32)
+    O.gossip_round(prob, X64, Q64)
+    for i in range(wl.n_workers):
+        for l in range(3):
+            ref = X64[i][l]
+            assert np.abs(X32[i][l] - ref).max() <= 1e-6 * max(np.abs(ref).max(), 1.0)
+    for e in range(wl.n_edges):
+        for l in range(3):
+            ref = Q64[e][l]
+            assert np.abs(Q32[e][l] - ref).max() <= 1e-6 * np.sqrt((ref ** 2).mean()) * 10
+
+
+# ------------------------------------------------- message sizes (tables)
+def test_vector_lengths_reproduce_the_printed_compression_ratios():
+    """Appendix 'Network architectures': the per-tensor 'Compression' column is
+    p*q / ((p+q)/2) -- one length-p or length-q vector per iteration.  The oracle's state
+    has exactly those lengths: Phat columns of length p, Q columns of length q."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "compression_ratios.txt"))
+            if l.strip() and not l.startswith("#")]
+    rng = np.random.default_rng(15)
+    for p, q, printed in [(int(a), int(b), int(c)) for a, b, c in rows]:
+        if p * q <= 64 * 576:       # run the oracle on the small ones to read its vector lengths
+            prob = make(2, [[0, 1]], 0.5, [(p, q)])
+            X, Q = rand_state(prob, rng)
+            info = O.gossip_round(prob, X, Q, want_phat=True)
+            sent_odd, sent_even = info.phat[0][0].size, Q[0][0].size
+        else:
+            sent_odd, sent_even = p, q
+        assert round(p * q / ((sent_odd + sent_even) / 2)) == printed

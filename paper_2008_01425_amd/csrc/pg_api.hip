@@ -1,0 +1,391 @@
+// C ABI of the PowerGossip library: context life cycle, layout queries, launch sequencing.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/powergossip.h"
+#include "pg_kernels.hip"
+#include "pg_plan.hpp"
+
+using namespace pg;
+
+namespace {
+
+enum Kind { K_SWEEP_P = 0, K_ORTH_P, K_SWEEP_Q, K_COMBINE_Q, K_UPDATE, K_UPDATE_SWEEP_P, K_COUNT };
+const char *const kKindName[K_COUNT] = {"sweep_p", "orth_p",  "sweep_q",
+                                        "combine_q", "update", "update_sweep_p"};
+
+struct ProfRec {
+    int kind;
+    double bytes;
+    hipEvent_t t0, t1;
+};
+
+}  // namespace
+
+struct pg_ctx {
+    Plan plan;
+    bool uploaded = false;
+    PairDesc *d_pairs = nullptr;
+    ColDesc *d_cols = nullptr;
+    RowTile *d_row_tiles = nullptr;
+    ColTile *d_col_tiles = nullptr;
+    EdgeLayerDesc *d_els = nullptr;
+    CombTile *d_comb = nullptr;
+    float **d_xs = nullptr;
+    std::vector<float *> xs_cached;
+    bool profiling = false;
+    std::vector<ProfRec> recs;
+    std::vector<hipEvent_t> free_events;
+};
+
+namespace {
+
+#define PG_HIP(call)                                 \
+    do {                                             \
+        hipError_t err__ = (call);                   \
+        if (err__ != hipSuccess) {                   \
+            (void)hipGetLastError();                 \
+            return err__ == hipErrorOutOfMemory ? PG_ERR_NOMEM : PG_ERR_DEVICE; \
+        }                                            \
+    } while (0)
+
+template <typename T>
+int upload_vec(T **dst, const std::vector<T> &src) {
+    size_t bytes = std::max<size_t>(src.size(), 1) * sizeof(T);
+    PG_HIP(hipMalloc((void **)dst, bytes));
+    if (!src.empty()) PG_HIP(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice));
+    return PG_OK;
+}
+
+int do_upload(pg_ctx *c) {
+    if (c->uploaded) return PG_OK;
+    Plan &P = c->plan;
+    std::vector<RowTile> rt;
+    for (auto &rc : P.row_classes) {
+        rc.dev_first = rt.size();
+        rt.insert(rt.end(), rc.tiles.begin(), rc.tiles.end());
+    }
+    std::vector<ColTile> ct;
+    for (auto &cc : P.col_classes) {
+        cc.dev_first = ct.size();
+        ct.insert(ct.end(), cc.tiles.begin(), cc.tiles.end());
+    }
+    int rc;
+    if ((rc = upload_vec(&c->d_pairs, P.pairs))) return rc;
+    if ((rc = upload_vec(&c->d_cols, P.cols))) return rc;
+    if ((rc = upload_vec(&c->d_row_tiles, rt))) return rc;
+    if ((rc = upload_vec(&c->d_col_tiles, ct))) return rc;
+    if ((rc = upload_vec(&c->d_els, P.els))) return rc;
+    if ((rc = upload_vec(&c->d_comb, P.comb_tiles))) return rc;
+    PG_HIP(hipMalloc((void **)&c->d_xs, sizeof(float *) * (size_t)P.n));
+    c->uploaded = true;
+    return PG_OK;
+}
+
+struct Launcher {
+    pg_ctx *c;
+    hipStream_t st;
+    float *qstate;
+    char *ws;
+    int status = PG_OK;
+
+    double *pw() const { return (double *)(ws + c->plan.ws_pw); }
+    double *qw() const { return (double *)(ws + c->plan.ws_qw); }
+    double *pdb() const { return (double *)(ws + c->plan.ws_pd); }
+    float *ph() const { return (float *)(ws + c->plan.ws_ph); }
+    int32_t *flags() const { return (int32_t *)(ws + c->plan.ws_flag); }
+
+    hipEvent_t get_event() {
+        if (!c->free_events.empty()) {
+            hipEvent_t e = c->free_events.back();
+            c->free_events.pop_back();
+            return e;
+        }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) status = PG_ERR_DEVICE;
+        return e;
+    }
+    void begin(int kind, double bytes) {
+        if (!c->profiling || status) return;
+        ProfRec r{kind, bytes, get_event(), get_event()};
+        if (status) return;
+        if (hipEventRecord(r.t0, st) != hipSuccess) status = PG_ERR_DEVICE;
+        c->recs.push_back(r);
+    }
+    void end() {
+        if (!c->profiling || status) return;
+        if (hipEventRecord(c->recs.back().t1, st) != hipSuccess) status = PG_ERR_DEVICE;
+    }
+    void check() {
+        if (hipGetLastError() != hipSuccess) status = PG_ERR_DEVICE;
+    }
+
+    template <int V, int RC, bool UPD, bool SWP>
+    void row_launch(const RowClass &rc) {
+        constexpr int M = (RC <= 2) ? 8 : (RC <= 4 ? 4 : 2);
+        row_kernel<V, RC, M, UPD, SWP><<<dim3((unsigned)rc.tiles.size()), dim3(kThreads), 0, st>>>(
+            c->d_row_tiles + rc.dev_first, c->d_pairs, c->d_cols, c->d_xs, qstate, ph(), pw());
+    }
+    template <int V, int RC>
+    void row_mode(const RowClass &rc, bool upd, bool swp) {
+        if (upd && swp) row_launch<V, RC, true, true>(rc);
+        else if (upd) row_launch<V, RC, true, false>(rc);
+        else row_launch<V, RC, false, true>(rc);
+    }
+    template <int V>
+    void row_cols(const RowClass &rc, bool upd, bool swp) {
+        switch (rc.RC) {
+            case 1: row_mode<V, 1>(rc, upd, swp); break;
+            case 2: row_mode<V, 2>(rc, upd, swp); break;
+            case 4: row_mode<V, 4>(rc, upd, swp); break;
+            case 8: row_mode<V, 8>(rc, upd, swp); break;
+            default: row_mode<V, 16>(rc, upd, swp); break;
+        }
+    }
+    // One pass of the row-owner kernels over every parameter: sweep, update, or both.
+    void rows(bool upd, bool swp) {
+        if (status) return;
+        int kind = upd ? (swp ? K_UPDATE_SWEEP_P : K_UPDATE) : K_SWEEP_P;
+        for (const RowClass &rc : c->plan.row_classes) {
+            if (rc.tiles.empty()) continue;
+            begin(kind, rc.elems * 4.0 * (upd ? 2.0 : 1.0));
+            switch (rc.V) {
+                case 4: row_cols<4>(rc, upd, swp); break;
+                case 2: row_cols<2>(rc, upd, swp); break;
+                default: row_cols<1>(rc, upd, swp); break;
+            }
+            check();
+            end();
+        }
+    }
+
+    template <int V>
+    void col_cols(const ColClass &cc) {
+        constexpr int U = 4;
+        dim3 grid((unsigned)cc.tiles.size()), block(kThreads);
+        const ColTile *tiles = c->d_col_tiles + cc.dev_first;
+        switch (cc.RC) {
+            case 1: col_kernel<V, 1, U><<<grid, block, 0, st>>>(tiles, c->d_pairs, c->d_cols, c->d_xs, ph(), qw()); break;
+            case 2: col_kernel<V, 2, U><<<grid, block, 0, st>>>(tiles, c->d_pairs, c->d_cols, c->d_xs, ph(), qw()); break;
+            case 4: col_kernel<V, 4, U><<<grid, block, 0, st>>>(tiles, c->d_pairs, c->d_cols, c->d_xs, ph(), qw()); break;
+            case 8: col_kernel<V, 8, U><<<grid, block, 0, st>>>(tiles, c->d_pairs, c->d_cols, c->d_xs, ph(), qw()); break;
+            default: col_kernel<V, 16, U><<<grid, block, 0, st>>>(tiles, c->d_pairs, c->d_cols, c->d_xs, ph(), qw()); break;
+        }
+    }
+    void sweep_q() {
+        if (status) return;
+        for (const ColClass &cc : c->plan.col_classes) {
+            if (cc.tiles.empty()) continue;
+            begin(K_SWEEP_Q, cc.elems * 4.0);
+            switch (cc.V) {
+                case 4: col_cols<4>(cc); break;
+                case 2: col_cols<2>(cc); break;
+                default: col_cols<1>(cc); break;
+            }
+            check();
+            end();
+        }
+    }
+    void orth_p() {
+        if (status || c->plan.els.empty()) return;
+        begin(K_ORTH_P, 0.0);
+        orth_kernel<256><<<dim3((unsigned)c->plan.els.size()), dim3(256), 0, st>>>(c->d_els, pw(), pdb(), ph(), flags());
+        check();
+        end();
+    }
+    void combine_q() {
+        if (status || c->plan.comb_tiles.empty()) return;
+        begin(K_COMBINE_Q, 0.0);
+        comb_kernel<<<dim3((unsigned)c->plan.comb_tiles.size()), dim3(kThreads), 0, st>>>(
+            c->d_comb, c->d_els, qw(), flags(), qstate);
+        check();
+        end();
+    }
+};
+
+int prepare(pg_ctx *c, float *const *worker_params, float *q_state, void *workspace, hipStream_t st) {
+    if (!c || !worker_params || !workspace) return PG_ERR_ARG;
+    const Plan &P = c->plan;
+    if (P.qstate_floats > 0 && !q_state) return PG_ERR_ARG;
+    if (((uintptr_t)q_state & 15) || ((uintptr_t)workspace & 255)) return PG_ERR_ARG;
+    for (int i = 0; i < P.n; ++i)
+        if (!worker_params[i] || ((uintptr_t)worker_params[i] & 15)) return PG_ERR_ARG;
+    int rc = do_upload(c);
+    if (rc) return rc;
+    bool same = c->xs_cached.size() == (size_t)P.n;
+    for (int i = 0; same && i < P.n; ++i) same = c->xs_cached[i] == worker_params[i];
+    if (!same) {
+        // Kernels already queued may still read the old table: drain the stream first.
+        PG_HIP(hipStreamSynchronize(st));
+        c->xs_cached.assign(worker_params, worker_params + P.n);
+        PG_HIP(hipMemcpy(c->d_xs, c->xs_cached.data(), sizeof(float *) * (size_t)P.n, hipMemcpyHostToDevice));
+    }
+    return PG_OK;
+}
+
+int run_rounds(pg_ctx *c, float *const *worker_params, float *q_state, void *workspace,
+               void *hip_stream, int rounds, bool fuse) {
+    hipStream_t st = (hipStream_t)hip_stream;
+    int rc = prepare(c, worker_params, q_state, workspace, st);
+    if (rc) return rc;
+    if (c->plan.n_edges == 0 || rounds == 0) return PG_OK;
+    Launcher L{c, st, q_state, (char *)workspace};
+    const int s = c->plan.steps;
+    for (int t = 0; t < rounds; ++t) {
+        for (int step = 0; step < s; ++step) {
+            // the first product of a later round was already formed by the fused update pass
+            if (!(fuse && t > 0 && step == 0)) L.rows(false, true);
+            L.orth_p();
+            L.sweep_q();
+            L.combine_q();
+        }
+        L.rows(true, fuse && t + 1 < rounds);
+    }
+    return L.status;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *pg_strerror(int status) {
+    switch (status) {
+        case PG_OK: return "ok";
+        case PG_ERR_ARG: return "invalid argument";
+        case PG_ERR_TOPOLOGY: return "invalid topology (index out of range, self-loop or duplicate edge)";
+        case PG_ERR_SHAPE: return "invalid layer shape";
+        case PG_ERR_NOMEM: return "out of memory";
+        case PG_ERR_DEVICE: return "HIP call failed";
+        default: return "unknown status";
+    }
+}
+
+int pg_init(pg_ctx **out, int n_workers, int n_edges, const int32_t *edges, const float *edge_w,
+            int n_layers, const int32_t *rows, const int32_t *cols, int rank, int power_steps) {
+    if (!out) return PG_ERR_ARG;
+    pg_ctx *c = new (std::nothrow) pg_ctx();
+    if (!c) return PG_ERR_NOMEM;
+    Tuning tune;
+    if (const char *e = getenv("PG_ROW_TILE_BYTES")) tune.row_tile_bytes = std::max(1024, atoi(e));
+    if (const char *e = getenv("PG_COL_TILE_BYTES")) tune.col_tile_bytes = std::max(1024, atoi(e));
+    int rc;
+    try {
+        rc = build_plan(c->plan, n_workers, n_edges, edges, edge_w, n_layers, rows, cols, rank,
+                        power_steps, tune);
+    } catch (const std::bad_alloc &) {
+        rc = PG_ERR_NOMEM;
+    }
+    if (rc) {
+        delete c;
+        return rc;
+    }
+    *out = c;
+    return PG_OK;
+}
+
+int pg_destroy(pg_ctx *c) {
+    if (!c) return PG_ERR_ARG;
+    if (c->uploaded) {
+        (void)hipDeviceSynchronize();
+        for (auto &r : c->recs) {
+            (void)hipEventDestroy(r.t0);
+            (void)hipEventDestroy(r.t1);
+        }
+        for (auto e : c->free_events) (void)hipEventDestroy(e);
+        (void)hipFree(c->d_pairs);
+        (void)hipFree(c->d_cols);
+        (void)hipFree(c->d_row_tiles);
+        (void)hipFree(c->d_col_tiles);
+        (void)hipFree(c->d_els);
+        (void)hipFree(c->d_comb);
+        (void)hipFree(c->d_xs);
+    }
+    delete c;
+    return PG_OK;
+}
+
+size_t pg_param_floats(const pg_ctx *c) { return c ? c->plan.param_floats : (size_t)-1; }
+size_t pg_layer_offset(const pg_ctx *c, int l) {
+    if (!c || l < 0 || l >= c->plan.n_layers) return (size_t)-1;
+    return (size_t)c->plan.layers[l].x_off;
+}
+int pg_layer_rank(const pg_ctx *c, int l) {
+    if (!c || l < 0 || l >= c->plan.n_layers) return -1;
+    return c->plan.layers[l].r;
+}
+size_t pg_qstate_floats(const pg_ctx *c) { return c ? c->plan.qstate_floats : (size_t)-1; }
+size_t pg_q_offset(const pg_ctx *c, int e, int l) {
+    if (!c || l < 0 || l >= c->plan.n_layers || e < 0 || e >= c->plan.n_edges) return (size_t)-1;
+    return (size_t)c->plan.q_off[(size_t)e * c->plan.n_layers + l];
+}
+size_t pg_workspace_bytes(const pg_ctx *c) { return c ? c->plan.ws_bytes : (size_t)-1; }
+size_t pg_ws_phat_offset(const pg_ctx *c, int e, int l) {
+    if (!c || l < 0 || l >= c->plan.n_layers || e < 0 || e >= c->plan.n_edges) return (size_t)-1;
+    return c->plan.ws_ph + 4 * (size_t)c->plan.ph_off[(size_t)e * c->plan.n_layers + l];
+}
+size_t pg_ws_flag_offset(const pg_ctx *c, int e, int l) {
+    if (!c || l < 0 || l >= c->plan.n_layers || e < 0 || e >= c->plan.n_edges) return (size_t)-1;
+    return c->plan.ws_flag + 4 * (size_t)c->plan.flag_off[(size_t)e * c->plan.n_layers + l];
+}
+size_t pg_message_floats(const pg_ctx *c) { return c ? c->plan.message_floats : (size_t)-1; }
+double pg_round_bytes(const pg_ctx *c, int fused) {
+    if (!c) return -1.0;
+    int passes = 2 * c->plan.steps + (fused ? 1 : 2);
+    return 4.0 * c->plan.n * c->plan.elems_per_worker * passes;
+}
+
+int pg_upload(pg_ctx *c) {
+    if (!c) return PG_ERR_ARG;
+    return do_upload(c);
+}
+
+int pg_round(pg_ctx *c, float *const *worker_params, float *q_state, void *workspace, void *hip_stream) {
+    return run_rounds(c, worker_params, q_state, workspace, hip_stream, 1, false);
+}
+
+int pg_run(pg_ctx *c, float *const *worker_params, float *q_state, void *workspace,
+           void *hip_stream, int rounds) {
+    if (rounds < 0) return PG_ERR_ARG;
+    return run_rounds(c, worker_params, q_state, workspace, hip_stream, rounds, true);
+}
+
+int pg_profile_enable(pg_ctx *c, int on) {
+    if (!c) return PG_ERR_ARG;
+    c->profiling = on != 0;
+    return PG_OK;
+}
+
+int pg_profile_collect(pg_ctx *c, pg_kernel_time *out, int max_out, int *n_out) {
+    if (!c || !out || !n_out || max_out < 0) return PG_ERR_ARG;
+    pg_kernel_time acc[K_COUNT];
+    for (int k = 0; k < K_COUNT; ++k) {
+        memset(&acc[k], 0, sizeof(acc[k]));
+        strncpy(acc[k].name, kKindName[k], sizeof(acc[k].name) - 1);
+    }
+    int status = PG_OK;
+    for (auto &r : c->recs) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(r.t1) != hipSuccess || hipEventElapsedTime(&ms, r.t0, r.t1) != hipSuccess) {
+            (void)hipGetLastError();
+            status = PG_ERR_DEVICE;
+        }
+        acc[r.kind].launches += 1;
+        acc[r.kind].ms += ms;
+        acc[r.kind].bytes += r.bytes;
+        c->free_events.push_back(r.t0);
+        c->free_events.push_back(r.t1);
+    }
+    c->recs.clear();
+    int n = 0;
+    for (int k = 0; k < K_COUNT && n < max_out; ++k)
+        if (acc[k].launches > 0) out[n++] = acc[k];
+    *n_out = n;
+    return status;
+}
+
+}  // extern "C"

@@ -1,0 +1,69 @@
+// Descriptor records shared by the host planner and the gfx950 kernels.
+//
+// Notation follows the paper: workers i, edges e = (a, b), layers l with X^l in R^{p x q},
+// rank r_l, projection state Q_e^l (q x r_l), P_e^l = D_e Q_e (p x r_l), Phat = orth(P).
+// A worker multiplies its matrix ONCE per sweep by the stacked columns of all its incident
+// edges ("Linearity", Section 3.1): R = deg(i) * r_l stacked columns j = slot * r_l + k.
+#pragma once
+#include <stdint.h>
+
+namespace pg {
+
+constexpr int kMaxCols = 16;   // largest R = deg(i) * r_l one pass supports
+constexpr int kThreads = 256;  // work-group size of the streaming kernels (4 wavefronts)
+
+// One stacked column of a (worker, layer) pair.
+struct ColDesc {
+    int64_t q_off;   // float offset of the Q column (edge, layer, k) in the state buffer
+    int64_t ph_off;  // float offset of the Phat column (edge, layer, k) in the workspace
+    float coef;      // +w_e when the worker is the edge's first endpoint, -w_e otherwise:
+                     // X_i -= coef * Phat Q'^T   (Eq. (2); equal and opposite on the two ends)
+    int32_t pad;
+};
+
+// One (worker, layer) pair.
+struct PairDesc {
+    int32_t worker, p, q, R;
+    int64_t x_off;     // float offset of the layer inside a worker buffer
+    int64_t pw_off;    // double offset of this pair's partial products X_i S: [seg][j][row]
+    int64_t qw_off;    // double offset of this pair's partial products X_i^T T: [blk][j][c]
+    int32_t col0;      // first ColDesc of the pair (R consecutive entries)
+    int32_t lpr;       // row-owner kernels: lanes that share one row (power of two <= 64)
+    int32_t nseg;      // row-owner kernels: column segments a row is split into
+    int32_t seg_len;   // floats per segment (multiple of lpr * V; the last one may be shorter)
+    int32_t lg;        // column-owner kernel: lanes side by side over columns (power of two <= 64)
+    int32_t nblk;      // column-owner kernel: row blocks
+    int32_t blk_rows;  // rows per block
+    int32_t pad;
+};
+
+// Row-owner tile: rows [row0, row0 + nrows) x column segment seg of one pair.
+struct RowTile {
+    int32_t pair, row0, nrows, seg;
+};
+
+// Column-owner tile: columns [c0, c0 + lg * V) x row block blk of one pair.
+struct ColTile {
+    int32_t pair, c0, blk, pad;
+};
+
+// One (edge, layer): where its partial products, Phat, state and flags live.
+struct EdgeLayerDesc {
+    int32_t p, q, r, nseg;
+    int32_t nblk, pad;
+    int64_t pwa_off, pwb_off;  // double offsets of this edge's column 0, segment 0, in worker a / b
+    int64_t pwa_seg, pwb_seg;  // stride between segments (R_a * p, R_b * p)
+    int64_t qwa_off, qwb_off;  // double offsets of this edge's column 0, block 0, in worker a / b
+    int64_t qwa_blk, qwb_blk;  // stride between blocks (R_a * q, R_b * q)
+    int64_t pd_off;            // double offset of the Gram-Schmidt scratch: r columns of p
+    int64_t ph_off;            // float offset of Phat: r columns of p
+    int64_t q_off;             // float offset of the state block: r columns of q
+    int64_t flag_off;          // int32 index of the r dropped-column flags
+};
+
+// combine_q tile: 256 consecutive elements of the r*q block of one (edge, layer).
+struct CombTile {
+    int32_t el, first;
+};
+
+}  // namespace pg

@@ -1,0 +1,329 @@
+#include "pg_plan.hpp"
+
+#include <algorithm>
+#include <cmath>
+#include <set>
+#include <utility>
+
+#include "../../include/powergossip.h"
+
+namespace pg {
+
+static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+static inline int pow2_ceil(int v) {
+    int r = 1;
+    while (r < v) r <<= 1;
+    return r;
+}
+
+int compiled_cols(int R) {
+    int rc = 1;
+    while (rc < R) rc <<= 1;
+    return rc;
+}
+
+int rows_unroll(int RC) {
+    if (RC <= 2) return 8;
+    if (RC <= 4) return 4;
+    return 2;
+}
+
+int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const float *edge_w,
+               int n_layers, const int32_t *rows, const int32_t *cols, int rank, int power_steps,
+               const Tuning &tune) {
+    if (n_workers < 1 || n_edges < 0 || n_layers < 1 || rank < 1 || power_steps < 1) return PG_ERR_ARG;
+    if ((n_edges > 0 && (!edges || !edge_w)) || !rows || !cols) return PG_ERR_ARG;
+
+    P.n = n_workers;
+    P.n_edges = n_edges;
+    P.n_layers = n_layers;
+    P.rank = rank;
+    P.steps = power_steps;
+    P.edges.assign(edges, edges + 2 * (size_t)n_edges);
+    P.edge_w.assign(edge_w, edge_w + n_edges);
+
+    // ---- topology (graph G and mixing weights W, assumption A4) ----
+    std::set<std::pair<int, int>> seen;
+    P.incident.assign(n_workers, {});
+    std::vector<double> wsum(n_workers, 0.0);
+    for (int e = 0; e < n_edges; ++e) {
+        int a = edges[2 * e], b = edges[2 * e + 1];
+        if (a < 0 || b < 0 || a >= n_workers || b >= n_workers || a == b) return PG_ERR_TOPOLOGY;
+        if (!seen.insert({std::min(a, b), std::max(a, b)}).second) return PG_ERR_TOPOLOGY;
+        float w = edge_w[e];
+        if (!std::isfinite(w) || w < 0.0f) return PG_ERR_ARG;
+        wsum[a] += w;
+        wsum[b] += w;
+        P.incident[a].push_back(e);
+        P.incident[b].push_back(e);
+    }
+    for (int i = 0; i < n_workers; ++i)
+        if (wsum[i] > 1.0 + 1e-6) return PG_ERR_ARG;  // the self-weight W_ii would be negative
+
+    // ---- layers: every weight and bias is its own matrix (Section 2) ----
+    P.layers.resize(n_layers);
+    int64_t off = 0;
+    P.elems_per_worker = 0;
+    P.message_floats = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        int p = rows[l], q = cols[l];
+        if (p < 1 || q < 1) return PG_ERR_SHAPE;
+        LayerInfo &L = P.layers[l];
+        L.p = p;
+        L.q = q;
+        L.r = std::min(rank, std::min(p, q));
+        L.V = (q % 4 == 0) ? 4 : (q % 2 == 0 ? 2 : 1);
+        L.x_off = off;
+        off = round_up(off + (int64_t)p * q, 4);
+        P.elems_per_worker += (double)p * q;
+        P.message_floats += (size_t)L.r * ((size_t)p + q);
+    }
+    P.param_floats = (size_t)off;
+    for (int i = 0; i < n_workers; ++i)
+        for (int l = 0; l < n_layers; ++l)
+            if ((int64_t)P.incident[i].size() * P.layers[l].r > kMaxCols) return PG_ERR_ARG;
+
+    // ---- projection state: edge-major, then layer, r_l columns of q_l floats ----
+    P.q_off.resize((size_t)n_edges * n_layers);
+    P.ph_off.resize((size_t)n_edges * n_layers);
+    P.flag_off.resize((size_t)n_edges * n_layers);
+    int64_t qo = 0, pho = 0, flo = 0, pdo = 0;
+    std::vector<int64_t> pd_off((size_t)n_edges * n_layers);
+    for (int e = 0; e < n_edges; ++e)
+        for (int l = 0; l < n_layers; ++l) {
+            const LayerInfo &L = P.layers[l];
+            size_t id = (size_t)e * n_layers + l;
+            P.q_off[id] = qo;
+            qo = round_up(qo + (int64_t)L.q * L.r, 4);
+            P.ph_off[id] = pho;
+            pho = round_up(pho + (int64_t)L.p * L.r, 4);
+            pd_off[id] = pdo;
+            pdo += (int64_t)L.p * L.r;
+            P.flag_off[id] = flo;
+            flo += L.r;
+        }
+    P.qstate_floats = (size_t)qo;
+
+    // ---- per-layer launch geometry ----
+    struct Geo {
+        int lpr, nseg, seg_len, rows_iter_base;  // row-owner
+        int lg, nblk, blk_rows;                  // column-owner
+    };
+    std::vector<Geo> geo(n_layers);
+    constexpr int kColUnroll = 4;
+    for (int l = 0; l < n_layers; ++l) {
+        const LayerInfo &L = P.layers[l];
+        Geo &g = geo[l];
+        int nv = L.q / L.V;  // vector loads per row
+        g.lpr = std::min(64, pow2_ceil(nv));
+        int chunk = g.lpr * L.V;  // floats one lane group covers per step
+        int nchunks = (L.q + chunk - 1) / chunk;
+        // Column segments keep a tile near the byte target when a single row is long.  The row
+        // blocking depends on the stacked column count; size for the best-connected worker.
+        size_t max_deg = 0;
+        for (int i = 0; i < n_workers; ++i) max_deg = std::max(max_deg, P.incident[i].size());
+        int rows_iter = 4 * (64 / g.lpr) * rows_unroll(compiled_cols(std::max<int>(1, (int)max_deg * L.r)));
+        int64_t chunk_bytes = (int64_t)rows_iter * chunk * 4;
+        int seg_chunks = (int)std::max<int64_t>(1, tune.row_tile_bytes / chunk_bytes);
+        g.nseg = (nchunks + seg_chunks - 1) / seg_chunks;
+        seg_chunks = (nchunks + g.nseg - 1) / g.nseg;
+        g.nseg = (nchunks + seg_chunks - 1) / seg_chunks;
+        g.seg_len = seg_chunks * chunk;
+        g.rows_iter_base = 4 * (64 / g.lpr);
+
+        // Column-owner kernel: lanes side by side over columns; pick the lane-group width that
+        // wastes the fewest lanes on the ragged end of a row (ties go to the wider group).
+        int best = 64;
+        double best_util = -1;
+        for (int lg : {64, 32, 16}) {
+            int lgc = std::min(lg, pow2_ceil(nv));
+            int groups = (nv + lgc - 1) / lgc;
+            double util = (double)nv / ((double)groups * lgc);
+            if (util > best_util + 0.05) {
+                best_util = util;
+                best = lgc;
+            }
+        }
+        g.lg = best;
+        int row_groups = 4 * (64 / g.lg);
+        int64_t row_bytes = (int64_t)g.lg * L.V * 4;
+        int64_t want = std::max<int64_t>(1, tune.col_tile_bytes / row_bytes);
+        int64_t unit = (int64_t)row_groups * kColUnroll;
+        int64_t br = round_up(want, unit);
+        if (br >= L.p) br = L.p;
+        g.blk_rows = (int)br;
+        g.nblk = (L.p + g.blk_rows - 1) / g.blk_rows;
+    }
+
+    // ---- (worker, layer) pairs with their stacked columns ----
+    P.pairs.resize((size_t)n_layers * n_workers);
+    P.cols.clear();
+    int64_t pwo = 0, qwo = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const LayerInfo &L = P.layers[l];
+        const Geo &g = geo[l];
+        for (int i = 0; i < n_workers; ++i) {
+            PairDesc &pd = P.pairs[(size_t)l * n_workers + i];
+            pd.worker = i;
+            pd.p = L.p;
+            pd.q = L.q;
+            pd.R = (int)P.incident[i].size() * L.r;
+            pd.x_off = L.x_off;
+            pd.pw_off = pwo;
+            pd.qw_off = qwo;
+            pd.col0 = (int)P.cols.size();
+            pd.lpr = g.lpr;
+            pd.nseg = g.nseg;
+            pd.seg_len = g.seg_len;
+            pd.lg = g.lg;
+            pd.nblk = g.nblk;
+            pd.blk_rows = g.blk_rows;
+            pd.pad = 0;
+            pwo += (int64_t)g.nseg * pd.R * L.p;
+            qwo += (int64_t)g.nblk * pd.R * L.q;
+            for (int e : P.incident[i])
+                for (int k = 0; k < L.r; ++k) {
+                    ColDesc c;
+                    size_t id = (size_t)e * n_layers + l;
+                    c.q_off = P.q_off[id] + (int64_t)k * L.q;
+                    c.ph_off = P.ph_off[id] + (int64_t)k * L.p;
+                    c.coef = (P.edges[2 * e] == i) ? P.edge_w[e] : -P.edge_w[e];
+                    c.pad = 0;
+                    P.cols.push_back(c);
+                }
+        }
+    }
+
+    // ---- (edge, layer) records ----
+    P.els.resize((size_t)n_layers * n_edges);
+    P.comb_tiles.clear();
+    for (int l = 0; l < n_layers; ++l) {
+        const LayerInfo &L = P.layers[l];
+        const Geo &g = geo[l];
+        for (int e = 0; e < n_edges; ++e) {
+            EdgeLayerDesc &d = P.els[(size_t)l * n_edges + e];
+            int a = P.edges[2 * e], b = P.edges[2 * e + 1];
+            const PairDesc &pa = P.pairs[(size_t)l * n_workers + a];
+            const PairDesc &pb = P.pairs[(size_t)l * n_workers + b];
+            auto slot = [&](int w) {
+                const auto &inc = P.incident[w];
+                return (int)(std::find(inc.begin(), inc.end(), e) - inc.begin());
+            };
+            int ja = slot(a) * L.r, jb = slot(b) * L.r;
+            size_t id = (size_t)e * n_layers + l;
+            d.p = L.p;
+            d.q = L.q;
+            d.r = L.r;
+            d.nseg = g.nseg;
+            d.nblk = g.nblk;
+            d.pad = 0;
+            d.pwa_off = pa.pw_off + (int64_t)ja * L.p;
+            d.pwb_off = pb.pw_off + (int64_t)jb * L.p;
+            d.pwa_seg = (int64_t)pa.R * L.p;
+            d.pwb_seg = (int64_t)pb.R * L.p;
+            d.qwa_off = pa.qw_off + (int64_t)ja * L.q;
+            d.qwb_off = pb.qw_off + (int64_t)jb * L.q;
+            d.qwa_blk = (int64_t)pa.R * L.q;
+            d.qwb_blk = (int64_t)pb.R * L.q;
+            d.pd_off = pd_off[id];
+            d.ph_off = P.ph_off[id];
+            d.q_off = P.q_off[id];
+            d.flag_off = P.flag_off[id];
+            int64_t total = (int64_t)L.r * L.q;
+            for (int64_t f = 0; f < total; f += kThreads)
+                P.comb_tiles.push_back({(int32_t)((size_t)l * n_edges + e), (int32_t)f});
+        }
+    }
+
+    // ---- workspace sections ----
+    size_t o = 0;
+    P.ws_pw = o;
+    o = (size_t)round_up(o + (size_t)pwo * 8, 256);
+    P.ws_qw = o;
+    o = (size_t)round_up(o + (size_t)qwo * 8, 256);
+    P.ws_pd = o;
+    o = (size_t)round_up(o + (size_t)pdo * 8, 256);
+    P.ws_ph = o;
+    o = (size_t)round_up(o + (size_t)pho * 4, 256);
+    P.ws_flag = o;
+    o = (size_t)round_up(o + (size_t)flo * 4, 256);
+    P.ws_bytes = std::max<size_t>(o, 256);
+
+    // ---- tiles, grouped by kernel instantiation, heaviest first ----
+    P.row_classes.clear();
+    P.col_classes.clear();
+    auto row_class = [&](int V, int RC) -> RowClass & {
+        for (auto &c : P.row_classes)
+            if (c.V == V && c.RC == RC) return c;
+        P.row_classes.push_back({V, RC, {}, 0, 0});
+        return P.row_classes.back();
+    };
+    auto col_class = [&](int V, int RC) -> ColClass & {
+        for (auto &c : P.col_classes)
+            if (c.V == V && c.RC == RC) return c;
+        P.col_classes.push_back({V, RC, {}, 0, 0});
+        return P.col_classes.back();
+    };
+    struct Weighted {
+        int64_t w;
+        RowTile t;
+    };
+    struct WeightedC {
+        int64_t w;
+        ColTile t;
+    };
+    std::vector<std::vector<Weighted>> rtmp;
+    std::vector<std::vector<WeightedC>> ctmp;
+    for (int l = 0; l < n_layers; ++l) {
+        const LayerInfo &L = P.layers[l];
+        const Geo &g = geo[l];
+        for (int i = 0; i < n_workers; ++i) {
+            int pair = l * n_workers + i;
+            const PairDesc &pd = P.pairs[pair];
+            if (pd.R == 0) continue;  // isolated worker: nothing to multiply or update
+            int RC = compiled_cols(pd.R);
+            RowClass &rc = row_class(L.V, RC);
+            size_t rci = &rc - &P.row_classes[0];
+            if (rtmp.size() <= rci) rtmp.resize(rci + 1);
+            int rows_iter = g.rows_iter_base * rows_unroll(RC);
+            int iters = 1;
+            if (g.nseg == 1) {
+                int64_t bytes_iter = (int64_t)rows_iter * L.q * 4;
+                iters = (int)std::max<int64_t>(1, tune.row_tile_bytes / bytes_iter);
+            }
+            int tile_rows = rows_iter * iters;
+            for (int r0 = 0; r0 < L.p; r0 += tile_rows)
+                for (int s = 0; s < g.nseg; ++s) {
+                    int nr = std::min(tile_rows, L.p - r0);
+                    int len = std::min(g.seg_len, L.q - s * g.seg_len);
+                    rtmp[rci].push_back({(int64_t)nr * len, {pair, r0, nr, s}});
+                }
+            rc.elems += (double)L.p * L.q;
+
+            ColClass &cc = col_class(L.V, RC);
+            size_t cci = &cc - &P.col_classes[0];
+            if (ctmp.size() <= cci) ctmp.resize(cci + 1);
+            int cw = g.lg * L.V;
+            for (int b = 0; b < g.nblk; ++b)
+                for (int c0 = 0; c0 < L.q; c0 += cw) {
+                    int nr = std::min(g.blk_rows, L.p - b * g.blk_rows);
+                    int len = std::min(cw, L.q - c0);
+                    ctmp[cci].push_back({(int64_t)nr * len, {pair, c0, b, 0}});
+                }
+            cc.elems += (double)L.p * L.q;
+        }
+    }
+    for (size_t k = 0; k < P.row_classes.size(); ++k) {
+        std::stable_sort(rtmp[k].begin(), rtmp[k].end(),
+                         [](const Weighted &x, const Weighted &y) { return x.w > y.w; });
+        for (auto &w : rtmp[k]) P.row_classes[k].tiles.push_back(w.t);
+    }
+    for (size_t k = 0; k < P.col_classes.size(); ++k) {
+        std::stable_sort(ctmp[k].begin(), ctmp[k].end(),
+                         [](const WeightedC &x, const WeightedC &y) { return x.w > y.w; });
+        for (auto &w : ctmp[k]) P.col_classes[k].tiles.push_back(w.t);
+    }
+    return PG_OK;
+}
+
+}  // namespace pg

@@ -1,0 +1,72 @@
+// Host-side planning of a PowerGossip context: validation, buffer layouts, per-worker
+// stacked-column tables and the tile lists the kernels are launched over.  No HIP here.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "pg_desc.h"
+
+namespace pg {
+
+struct LayerInfo {
+    int p, q, r;        // r = min(rank, p, q)
+    int V;              // floats per vector load: 4, 2 or 1 (largest that divides q)
+    int64_t x_off;      // float offset inside a worker buffer
+};
+
+// Tiles of one kernel instantiation: vector width V and compiled column count RC >= R.
+struct RowClass {
+    int V, RC;
+    std::vector<RowTile> tiles;
+    size_t dev_first = 0;   // index of the first tile in the uploaded table
+    double elems = 0;       // parameter elements covered (for byte accounting)
+};
+struct ColClass {
+    int V, RC;
+    std::vector<ColTile> tiles;
+    size_t dev_first = 0;
+    double elems = 0;
+};
+
+struct Tuning {
+    int row_tile_bytes = 96 * 1024;  // target parameter bytes per row-owner tile
+    int col_tile_bytes = 128 * 1024; // target parameter bytes per column-owner tile
+};
+
+struct Plan {
+    int n = 0, n_edges = 0, n_layers = 0, rank = 0, steps = 0;
+    std::vector<int32_t> edges;   // 2 * n_edges
+    std::vector<float> edge_w;
+    std::vector<LayerInfo> layers;
+    std::vector<std::vector<int>> incident;  // per worker: edge ids in edge-list order
+
+    size_t param_floats = 0, qstate_floats = 0, message_floats = 0;
+    double elems_per_worker = 0;             // N = sum p*q
+    std::vector<int64_t> q_off;              // [e * L + l]
+
+    // workspace sections (byte offsets) and their sizes
+    size_t ws_pw = 0, ws_qw = 0, ws_pd = 0, ws_ph = 0, ws_flag = 0, ws_bytes = 0;
+    std::vector<int64_t> ph_off;             // [e * L + l] float offset inside the Phat section
+    std::vector<int64_t> flag_off;           // [e * L + l] int32 index inside the flag section
+
+    std::vector<PairDesc> pairs;             // [l * n + i]
+    std::vector<ColDesc> cols;
+    std::vector<EdgeLayerDesc> els;          // [l * n_edges + e]
+    std::vector<CombTile> comb_tiles;
+    std::vector<RowClass> row_classes;
+    std::vector<ColClass> col_classes;
+    int orth_threads = 256;
+};
+
+// Rows one work-group covers per pass for a compiled column count (register blocking).
+int rows_unroll(int RC);
+// Smallest compiled column count >= R (1, 2, 4, 8, 16).
+int compiled_cols(int R);
+
+// Returns PG_OK or a negative status; on success `plan` is complete.
+int build_plan(Plan &plan, int n_workers, int n_edges, const int32_t *edges, const float *edge_w,
+               int n_layers, const int32_t *rows, const int32_t *cols, int rank, int power_steps,
+               const Tuning &tune);
+
+}  // namespace pg

@@ -1,0 +1,198 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Tolerances: 1e-5 relative per element after one round, 1e-4 after
+ten (rel_err in parity_util: |g - o| / max(|o|, rms(o)))."""
+import numpy as np
+import pytest
+
+from paper_2008_01425_amd import workloads as W
+from parity_util import TOL_1, TOL_10, compare_state, oracle_rounds, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _gb(wl, layers=None):
+    from paper_2008_01425_amd.device import GossipBuffers
+    gb = GossipBuffers.from_workload(wl, fill=False)
+    gb.fill_from_workload(wl, layers)
+    return gb
+
+
+def _custom(name, n, edges, w, shapes, rank, steps, sigma=0.05, seed=1):
+    ew = np.full((len(edges),), w, dtype=np.float32) if np.isscalar(w) else np.asarray(w, np.float32)
+    return W.Workload(name, n, np.asarray(edges, dtype=np.int32).reshape(-1, 2), ew, shapes, rank,
+                      steps, sigma, 10, seed)
+
+
+def _check(wl, rounds, tol, fused=False, layers=None, two_calls=False):
+    layers = list(range(len(wl.shapes))) if layers is None else list(layers)
+    print(f"case {wl.name} rounds={rounds} fused={fused} layers={layers[:6]}", flush=True)
+    gb = _gb(wl, layers)
+    X, Q = wl.all_params(layers), wl.all_q(layers)
+    if fused:
+        if two_calls:
+            gb.run(rounds - rounds // 2)
+            gb.run(rounds // 2)
+        else:
+            gb.run(rounds)
+    else:
+        for _ in range(rounds):
+            gb.round()
+    info = oracle_rounds(wl, X, Q, rounds, layers)
+    worst = compare_state(gb, X, Q, layers, tol, what=wl.name, phat=info.phat)
+    for j, l in enumerate(layers):
+        for e in range(gb.n_edges):
+            assert np.array_equal(gb.get_flags(e, l), info.degenerate[j][e])
+    print("   worst rel err", worst, flush=True)
+    gb.close()
+    return worst
+
+
+# ------------------------------------------------------------------ the named configurations
+def test_tiny_one_round():
+    _check(W.get("tiny"), 1, TOL_1)
+
+
+def test_tiny_ten_rounds():
+    _check(W.get("tiny"), 10, TOL_10)
+
+
+def test_tiny_ten_rounds_fused_run():
+    _check(W.get("tiny"), 10, TOL_10, fused=True)
+
+
+def test_resnet20_one_round_and_ten():
+    _check(W.get("resnet20"), 1, TOL_1)
+    _check(W.get("resnet20"), 10, TOL_10, fused=True)
+
+
+# ------------------------------------------------------------------ shapes, ranks, topologies
+SHAPES_RAGGED = [(37, 27), (130, 50), (9, 147), (300, 260), (700, 1), (5, 3), (1, 8), (64, 1028)]
+
+
+@pytest.mark.parametrize("rank,steps", [(1, 1), (2, 1), (4, 2), (3, 1)])
+def test_ragged_shapes_ring(rank, steps):
+    wl = _custom(f"ragged_r{rank}s{steps}", 5, W.ring_edges(5), 1 / 3, SHAPES_RAGGED, rank, steps)
+    _check(wl, 1, TOL_1)
+    _check(wl, 3, TOL_10, fused=True, two_calls=True)
+
+
+def test_torus_rank4_two_steps():
+    wl = _custom("torus3x3", 9, W.torus_edges(3, 3), 1 / 5, [(200, 650), (33, 12), (40, 1)], 4, 2)
+    _check(wl, 1, TOL_1)
+    _check(wl, 4, TOL_10, fused=True)
+
+
+def test_irregular_graph_with_isolated_and_leaf_workers():
+    edges = [[0, 1], [2, 0], [0, 3], [3, 1]]          # worker 4 has no edge; degrees 3, 2, 1, 2, 0
+    wl = _custom("irregular", 5, edges, [0.3, 0.2, 0.25, 0.4], [(48, 36), (17, 1), (20, 64)], 2, 1)
+    _check(wl, 2, TOL_10)
+    _check(wl, 2, TOL_10, fused=True)
+
+
+def test_many_tiles_and_tail_rows():
+    wl = _custom("tall", 3, W.ring_edges(3), 1 / 3, [(4099, 68), (1031, 516), (70, 4612)], 2, 1)
+    _check(wl, 1, TOL_1)
+    _check(wl, 2, TOL_10, fused=True)
+
+
+# ------------------------------------------------------------------ degenerate cases
+def test_identical_workers_are_a_fixed_point():
+    from paper_2008_01425_amd.device import GossipBuffers
+    wl = _custom("same", 4, W.ring_edges(4), 1 / 3, [(40, 24), (12, 1)], 2, 2, sigma=0.0)
+    gb = GossipBuffers.from_workload(wl)
+    x0 = [[gb.get_layer(i, l) for l in range(2)] for i in range(4)]
+    q0 = [[gb.get_q(e, l) for l in range(2)] for e in range(4)]
+    gb.run(3)
+    gb.round()
+    for i in range(4):
+        for l in range(2):
+            assert np.array_equal(gb.get_layer(i, l), x0[i][l])
+    for e in range(4):
+        for l in range(2):
+            assert np.array_equal(gb.get_q(e, l), q0[e][l])
+            assert gb.get_flags(e, l).all()
+            assert not gb.get_phat(e, l).any()
+    gb.close()
+
+
+def test_rank_deficient_difference_drops_a_column():
+    from paper_2008_01425_amd.device import GossipBuffers
+    from oracle import pg_oracle as O
+    rng = np.random.default_rng(5)
+    p, q = 48, 40
+    base = rng.standard_normal((p, q)).astype(np.float32)
+    # a difference that is exactly rank one in float: small-integer outer product
+    u = rng.integers(-3, 4, p).astype(np.float32)
+    v = rng.integers(-3, 4, q).astype(np.float32)
+    base = np.round(base * 64) / 64
+    Xa, Xb = (base + np.outer(u, v) / 64).astype(np.float32), base.copy()
+    Q0 = rng.standard_normal((2, q)).astype(np.float32)
+    gb = GossipBuffers(2, [[0, 1]], [0.5], [(p, q)], 2, 1)
+    gb.set_layer(0, 0, Xa); gb.set_layer(1, 0, Xb); gb.set_q(0, 0, Q0)
+    gb.round()
+    prob = O.Problem(2, np.array([[0, 1]]), np.array([0.5]), [(p, q)], 2, 1)
+    X, Q = [[Xa.copy()], [Xb.copy()]], [[Q0.copy()]]
+    info = O.gossip_round(prob, X, Q, want_phat=True)
+    assert info.degenerate[0].tolist() == [[0, 1]]
+    assert gb.get_flags(0, 0).tolist() == [0, 1]
+    assert np.array_equal(gb.get_q(0, 0)[1], Q0[1])
+    assert rel_err(gb.get_q(0, 0)[0], Q[0][0][0]) <= TOL_1
+    assert rel_err(gb.get_layer(0, 0), X[0][0]) <= TOL_1
+    assert rel_err(gb.get_layer(1, 0), X[1][0]) <= TOL_1
+    gb.close()
+
+
+def test_no_edges_is_a_no_op():
+    from paper_2008_01425_amd.device import GossipBuffers
+    gb = GossipBuffers(2, np.zeros((0, 2), np.int32), np.zeros((0,), np.float32), [(8, 4)], 1, 1)
+    a = np.arange(32, dtype=np.float32).reshape(8, 4)
+    gb.set_layer(0, 0, a)
+    gb.round(); gb.run(2)
+    assert np.array_equal(gb.get_layer(0, 0), a)
+    gb.close()
+
+
+def test_results_are_deterministic():
+    wl = W.get("resnet20")
+    outs = []
+    for _ in range(2):
+        gb = _gb(wl)
+        gb.run(3)
+        outs.append((gb.x[3].cpu().numpy().copy(), gb.q.cpu().numpy().copy()))
+        gb.close()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_run_equals_repeated_round_bitwise():
+    wl = _custom("fuse_eq", 6, W.ring_edges(6), 1 / 3, [(96, 260), (50, 1), (31, 27)], 2, 2)
+    a, b = _gb(wl), _gb(wl)
+    a.run(4)
+    for _ in range(4):
+        b.round()
+    for i in range(6):
+        assert np.array_equal(a.x[i].cpu().numpy(), b.x[i].cpu().numpy())
+    assert np.array_equal(a.q.cpu().numpy(), b.q.cpu().numpy())
+    a.close(); b.close()
+
+
+# ------------------------------------------------------------------ full-size configurations
+def test_vgg16_full_size_one_round_rank1():
+    _check(W.get("vgg16_r1"), 1, TOL_1)
+
+
+def test_vgg16_full_size_rank2_sampled_layers_fused_rounds():
+    # every layer class once: first conv (q = 27), a mid conv, the widest conv, the classifier
+    _check(W.get("vgg16_r2"), 3, TOL_10, fused=True, layers=[0, 3, 9, 13])
+
+
+def test_lstm_full_size_sampled_layer():
+    _check(W.get("lstm"), 1, TOL_1, layers=[2])
+
+
+def test_resnet50_full_size_sampled_layers():
+    wl = W.get("resnet50")
+    big = [l for l, (p, q) in enumerate(wl.shapes) if (p, q) in ((64, 147), (256, 2304), (1000, 2048), (2048, 1))]
+    picks = []
+    for shape in ((64, 147), (256, 2304), (1000, 2048), (2048, 1)):
+        picks.append(next(l for l in big if wl.shapes[l] == shape))
+    _check(wl, 2, TOL_10, fused=True, layers=picks)

@@ -125,68 +125,62 @@ struct Launcher {
         if (hipGetLastError() != hipSuccess) status = PG_ERR_DEVICE;
     }
 
-    template <int V, int RC, bool UPD, bool SWP>
+    template <int RC, bool UPD, bool SWP>
     void row_launch(const RowClass &rc) {
-        constexpr int M = (RC <= 2) ? 8 : (RC <= 4 ? 4 : 2);
-        row_kernel<V, RC, M, UPD, SWP><<<dim3((unsigned)rc.tiles.size()), dim3(kThreads), 0, st>>>(
-            c->d_row_tiles + rc.dev_first, c->d_pairs, c->d_cols, c->d_xs, qstate, ph(), pw());
+        constexpr int M = (RC <= 2) ? 8 : (RC <= 4 ? 4 : (RC <= 8 ? 2 : 1));
+        const int n = (int)rc.tiles.size();
+        row_kernel<RC, M, UPD, SWP><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
+            c->d_row_tiles + rc.dev_first, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, qstate,
+            ph(), pw());
     }
-    template <int V, int RC>
+    template <int RC>
     void row_mode(const RowClass &rc, bool upd, bool swp) {
-        if (upd && swp) row_launch<V, RC, true, true>(rc);
-        else if (upd) row_launch<V, RC, true, false>(rc);
-        else row_launch<V, RC, false, true>(rc);
+        if (upd && swp) row_launch<RC, true, true>(rc);
+        else if (upd) row_launch<RC, true, false>(rc);
+        else row_launch<RC, false, true>(rc);
     }
-    template <int V>
-    void row_cols(const RowClass &rc, bool upd, bool swp) {
-        switch (rc.RC) {
-            case 1: row_mode<V, 1>(rc, upd, swp); break;
-            case 2: row_mode<V, 2>(rc, upd, swp); break;
-            case 4: row_mode<V, 4>(rc, upd, swp); break;
-            case 8: row_mode<V, 8>(rc, upd, swp); break;
-            default: row_mode<V, 16>(rc, upd, swp); break;
-        }
-    }
-    // One pass of the row-owner kernels over every parameter: sweep, update, or both.
+    // One pass of the row-owner kernels over every parameter, front to back: sweep, update, or both.
     void rows(bool upd, bool swp) {
         if (status) return;
         int kind = upd ? (swp ? K_UPDATE_SWEEP_P : K_UPDATE) : K_SWEEP_P;
         for (const RowClass &rc : c->plan.row_classes) {
             if (rc.tiles.empty()) continue;
             begin(kind, rc.elems * 4.0 * (upd ? 2.0 : 1.0));
-            switch (rc.V) {
-                case 4: row_cols<4>(rc, upd, swp); break;
-                case 2: row_cols<2>(rc, upd, swp); break;
-                default: row_cols<1>(rc, upd, swp); break;
+            switch (rc.RC) {
+                case 1: row_mode<1>(rc, upd, swp); break;
+                case 2: row_mode<2>(rc, upd, swp); break;
+                case 4: row_mode<4>(rc, upd, swp); break;
+                case 8: row_mode<8>(rc, upd, swp); break;
+                default: row_mode<16>(rc, upd, swp); break;
             }
             check();
             end();
         }
     }
 
-    template <int V>
-    void col_cols(const ColClass &cc) {
-        constexpr int U = 4;
-        dim3 grid((unsigned)cc.tiles.size()), block(kThreads);
-        const ColTile *tiles = c->d_col_tiles + cc.dev_first;
-        switch (cc.RC) {
-            case 1: col_kernel<V, 1, U><<<grid, block, 0, st>>>(tiles, c->d_pairs, c->d_cols, c->d_xs, ph(), qw()); break;
-            case 2: col_kernel<V, 2, U><<<grid, block, 0, st>>>(tiles, c->d_pairs, c->d_cols, c->d_xs, ph(), qw()); break;
-            case 4: col_kernel<V, 4, U><<<grid, block, 0, st>>>(tiles, c->d_pairs, c->d_cols, c->d_xs, ph(), qw()); break;
-            case 8: col_kernel<V, 8, U><<<grid, block, 0, st>>>(tiles, c->d_pairs, c->d_cols, c->d_xs, ph(), qw()); break;
-            default: col_kernel<V, 16, U><<<grid, block, 0, st>>>(tiles, c->d_pairs, c->d_cols, c->d_xs, ph(), qw()); break;
-        }
-    }
+    // The Q-sweep walks the parameters back to front: it starts on what the pass before it
+    // (always a front-to-back row pass) touched last.
     void sweep_q() {
         if (status) return;
+        constexpr int U = 8;
         for (const ColClass &cc : c->plan.col_classes) {
             if (cc.tiles.empty()) continue;
             begin(K_SWEEP_Q, cc.elems * 4.0);
-            switch (cc.V) {
-                case 4: col_cols<4>(cc); break;
-                case 2: col_cols<2>(cc); break;
-                default: col_cols<1>(cc); break;
+            const int n = (int)cc.tiles.size();
+            dim3 grid((unsigned)n), block(kThreads);
+            const ColTile *tiles = c->d_col_tiles + cc.dev_first;
+            // LDS: the staged Phat slice, later reused for the cross-wavefront sums
+            size_t lds = std::max((size_t)cc.max_rows * cc.RC * sizeof(float),
+                                  (size_t)(kThreads / 64 - 1) * 64 * 4 * sizeof(double));
+#define PG_COL(RCV) col_kernel<RCV, U><<<grid, block, lds, st>>>(tiles, n, /*reverse=*/1, c->d_pairs, c->d_cols, c->d_xs, ph(), qw())
+            switch (cc.RC) {
+                case 1: PG_COL(1); break;
+                case 2: PG_COL(2); break;
+                case 4: PG_COL(4); break;
+                case 8: PG_COL(8); break;
+                default: PG_COL(16); break;
             }
+#undef PG_COL
             check();
             end();
         }

@@ -10,7 +10,8 @@
 namespace pg {
 
 constexpr int kMaxCols = 16;   // largest R = deg(i) * r_l one pass supports
-constexpr int kThreads = 256;  // work-group size of the streaming kernels (4 wavefronts)
+constexpr int kThreads = 256;  // work-group size of the column-owner and combine kernels (4 wavefronts)
+constexpr int kRowThreads = 64;  // row-owner kernels: one wavefront per tile
 
 // One stacked column of a (worker, layer) pair.
 struct ColDesc {
@@ -34,7 +35,7 @@ struct PairDesc {
     int32_t lg;        // column-owner kernel: lanes side by side over columns (power of two <= 64)
     int32_t nblk;      // column-owner kernel: row blocks
     int32_t blk_rows;  // rows per block
-    int32_t pad;
+    int32_t V;         // floats per vector load on this layer: 4, 2 or 1 (largest that divides q)
 };
 
 // Row-owner tile: rows [row0, row0 + nrows) x column segment seg of one pair.

@@ -15,29 +15,60 @@
 
 namespace pg {
 
+#define PG_GLOBAL __attribute__((address_space(1)))
+// Instruction-scheduling fence: nothing is moved across it.
+#define PG_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// V floats moved by one load / store instruction (128, 64 or 32 bits).
 template <int V>
-struct alignas(4 * V) FV {
-    float a[V];
+struct VecT {
+    typedef float T __attribute__((ext_vector_type(V)));
 };
 
+// Loads and stores through explicitly global pointers: parameter buffers are reached through a
+// pointer table, so the compiler cannot see that they are global and would emit flat accesses.
 template <int V>
-__device__ __forceinline__ FV<V> ldv(const float *p) {
-    return *reinterpret_cast<const FV<V> *>(p);
+__device__ __forceinline__ typename VecT<V>::T ldg(const float *p) {
+    return *(const PG_GLOBAL typename VecT<V>::T *)p;
 }
 template <int V>
-__device__ __forceinline__ void stv(float *p, const FV<V> &v) {
-    *reinterpret_cast<FV<V> *>(p) = v;
+__device__ __forceinline__ void stg(float *p, typename VecT<V>::T v) {
+    *(PG_GLOBAL typename VecT<V>::T *)p = v;
 }
+__device__ __forceinline__ float ldg1(const float *p) { return *(const PG_GLOBAL float *)p; }
 
-// Sum over the `width` (power of two) consecutive lanes that contain this lane.
+// ---- wavefront reductions on the DPP / swizzle network --------------------------------
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov(double v) {
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, false);
+    hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double swizzle_xor16(double v) {
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_ds_swizzle(lo, 0x401f);  // bit mode: and 0x1f, or 0, xor 0x10
+    hi = __builtin_amdgcn_ds_swizzle(hi, 0x401f);
+    return __hiloint2double(hi, lo);
+}
+// Sum over the `width` (power of two) consecutive lanes that contain this lane; every lane of
+// the group receives the sum.  Lane exchanges: quad permutes (1, 2), mirror within 8 and within
+// 16 lanes (each lane of a quad / octet already holds that quad's / octet's sum), swizzle across
+// 16, and a cross-half shuffle for 64.
 __device__ __forceinline__ double group_sum(double v, int width) {
-    for (int o = width >> 1; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+    if (width > 1) v += dpp_mov<0xB1>(v);   // quad_perm [1,0,3,2]
+    if (width > 2) v += dpp_mov<0x4E>(v);   // quad_perm [2,3,0,1]
+    if (width > 4) v += dpp_mov<0x141>(v);  // row_half_mirror
+    if (width > 8) v += dpp_mov<0x140>(v);  // row_mirror
+    if (width > 16) v += swizzle_xor16(v);
+    if (width > 32) v += __shfl_xor(v, 32);
     return v;
 }
 
 // ---------------------------------------------------------------------------------------
-// Row-owner kernel.  A group of `lpr` lanes walks along M rows of X_i at once with vector
-// loads; per column step it holds the RC stacked right-hand-side columns for its slice.
+// Row-owner kernel: one wavefront per tile.  A group of `lpr` lanes walks along M rows of X_i
+// at once with vector loads; per column step it holds the RC stacked right-hand-side columns
+// for its slice.  The loads of step c + 1 are issued before the arithmetic of step c.
 //   SWEEP : Pw[j][row] = sum_c X[row, c] * Q_j[c]            (Algorithm 2, odd iteration:
 //           p_i = X_i v for every incident edge's v in one read of X_i)
 //   UPDATE: X[row, c] -= sum_j coef_j * Phat_j[row] * Q'_j[c] (Eq. (2) summed over the edges)
@@ -45,24 +76,22 @@ __device__ __forceinline__ double group_sum(double v, int width) {
 //           round's right-hand side is exactly the Q' just applied (warm start).
 // ---------------------------------------------------------------------------------------
 template <int V, int RC, int M, bool UPDATE, bool SWEEP>
-__global__ void __launch_bounds__(kThreads)
-row_kernel(const RowTile *__restrict__ tiles, const PairDesc *__restrict__ pairs,
-           const ColDesc *__restrict__ cols, float *const *__restrict__ xs,
-           const float *__restrict__ qstate, const float *__restrict__ phat,
-           double *__restrict__ pw) {
-    const RowTile t = tiles[blockIdx.x];
-    const PairDesc pd = pairs[t.pair];
-    float *__restrict__ X = xs[pd.worker] + pd.x_off;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+__device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
+                                         const ColDesc *__restrict__ cols, float *X,
+                                         const float *__restrict__ qstate,
+                                         const float *__restrict__ phat, double *__restrict__ pw) {
+    typedef typename VecT<V>::T vec;
+    const int lane = threadIdx.x;
     const int lpr = pd.lpr;
     const int lpr_shift = __ffs(lpr) - 1;
     const int sub = lane & (lpr - 1);
-    const int grp = wave * (64 >> lpr_shift) + (lane >> lpr_shift);
-    const int ngrp = (kThreads / 64) * (64 >> lpr_shift);
+    const int grp = lane >> lpr_shift;
+    const int ngrp = 64 >> lpr_shift;
     const int q = pd.q, R = pd.R;
     const int c_begin = t.seg * pd.seg_len;
     const int c_end = min(q, c_begin + pd.seg_len);
     const int row_end = t.row0 + t.nrows;
+    const int step = lpr * V;
 
     const float *qcol[RC];
     const float *phc[RC];
@@ -76,19 +105,22 @@ row_kernel(const RowTile *__restrict__ tiles, const PairDesc *__restrict__ pairs
     }
 
     for (int rbase = t.row0 + grp * M; rbase < row_end; rbase += ngrp * M) {
-        int rowi[M];
+        float *xrow[M];
         bool ok[M];
+        int rowi[M];
 #pragma unroll
         for (int m = 0; m < M; ++m) {
             ok[m] = rbase + m < row_end;
             rowi[m] = ok[m] ? rbase + m : row_end - 1;
+            xrow[m] = X + (int64_t)rowi[m] * q;
         }
         double cp[M][RC];
         if (UPDATE) {
 #pragma unroll
             for (int m = 0; m < M; ++m)
 #pragma unroll
-                for (int j = 0; j < RC; ++j) cp[m][j] = (double)coef[j] * (double)phc[j][rowi[m]];
+                for (int j = 0; j < RC; ++j)
+                    cp[m][j] = (double)coef[j] * (double)ldg1(phc[j] + rowi[m]);
         }
         double acc[M][RC];
 #pragma unroll
@@ -96,34 +128,76 @@ row_kernel(const RowTile *__restrict__ tiles, const PairDesc *__restrict__ pairs
 #pragma unroll
             for (int j = 0; j < RC; ++j) acc[m][j] = 0.0;
 
-        for (int c = c_begin + sub * V; c < c_end; c += lpr * V) {
-            FV<V> qv[RC];
+        // Many stacked columns: only X is prefetched a step ahead, the (cache-resident) Q slice
+        // is fetched at the point of use, so that one Q buffer fits in registers.
+        constexpr bool QPF = RC <= 4;
+        auto load = [&](int c, vec(&xv)[M], vec(&qv)[RC]) {
+            if (QPF) {
 #pragma unroll
-            for (int j = 0; j < RC; ++j) qv[j] = ldv<V>(qcol[j] + c);
-            FV<V> xv[M];
+                for (int j = 0; j < RC; ++j) qv[j] = ldg<V>(qcol[j] + c);
+            }
 #pragma unroll
-            for (int m = 0; m < M; ++m) xv[m] = ldv<V>(X + (int64_t)rowi[m] * q + c);
-            if (UPDATE) {
+            for (int m = 0; m < M; ++m) xv[m] = ldg<V>(xrow[m] + c);
+        };
+        auto process = [&](int c, vec(&xv)[M], vec(&qv)[RC]) {
+            if (!QPF) {
 #pragma unroll
-                for (int m = 0; m < M; ++m) {
+                for (int j = 0; j < RC; ++j) qv[j] = ldg<V>(qcol[j] + c);
+            }
+            double qd[RC][V];
+#pragma unroll
+            for (int j = 0; j < RC; ++j)
+#pragma unroll
+                for (int v = 0; v < V; ++v) qd[j][v] = (double)qv[j][v];
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                double xd[V];
+#pragma unroll
+                for (int v = 0; v < V; ++v) xd[v] = (double)xv[m][v];
+                if (UPDATE) {
 #pragma unroll
                     for (int v = 0; v < V; ++v) {
-                        double x = (double)xv[m].a[v];
 #pragma unroll
-                        for (int j = 0; j < RC; ++j) x = fma(-cp[m][j], (double)qv[j].a[v], x);
-                        xv[m].a[v] = (float)x;
+                        for (int j = 0; j < RC; ++j) xd[v] = fma(-cp[m][j], qd[j][v], xd[v]);
+                        xv[m][v] = (float)xd[v];
+                        xd[v] = (double)xv[m][v];  // the sweep uses the stored (rounded) value
                     }
-                    if (ok[m]) stv<V>(X + (int64_t)rowi[m] * q + c, xv[m]);
+                    if (ok[m]) stg<V>(xrow[m] + c, xv[m]);
                 }
-            }
-            if (SWEEP) {
-#pragma unroll
-                for (int m = 0; m < M; ++m)
+                if (SWEEP) {
 #pragma unroll
                     for (int j = 0; j < RC; ++j)
 #pragma unroll
-                        for (int v = 0; v < V; ++v)
-                            acc[m][j] = fma((double)xv[m].a[v], (double)qv[j].a[v], acc[m][j]);
+                        for (int v = 0; v < V; ++v) acc[m][j] = fma(xd[v], qd[j][v], acc[m][j]);
+                }
+            }
+        };
+
+        int c = c_begin + sub * V;
+        if (c < c_end) {
+            vec xa[M], qa[RC], xb[M], qb[RC];
+            int rem = (c_end - c - 1) / step;  // steps after the first one
+            // PG_FENCE keeps the compiler from sinking a prefetch below the arithmetic it overlaps
+            load(c, xa, qa);
+            while (rem >= 2) {
+                load(c + step, xb, qb);
+                PG_FENCE();
+                process(c, xa, qa);
+                PG_FENCE();
+                load(c + 2 * step, xa, qa);
+                PG_FENCE();
+                process(c + step, xb, qb);
+                PG_FENCE();
+                c += 2 * step;
+                rem -= 2;
+            }
+            if (rem == 1) {
+                load(c + step, xb, qb);
+                PG_FENCE();
+                process(c, xa, qa);
+                process(c + step, xb, qb);
+            } else {
+                process(c, xa, qa);
             }
         }
         if (SWEEP) {
@@ -139,22 +213,37 @@ row_kernel(const RowTile *__restrict__ tiles, const PairDesc *__restrict__ pairs
     }
 }
 
+// One wavefront per tile; `reverse` walks the tile list backwards so that a pass can start on
+// the data the previous pass touched last (still resident in the memory-side cache).
+template <int RC, int M, bool UPDATE, bool SWEEP>
+__global__ void __launch_bounds__(kRowThreads)
+row_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
+           const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
+           float *const *__restrict__ xs, const float *__restrict__ qstate,
+           const float *__restrict__ phat, double *__restrict__ pw) {
+    const RowTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
+    const PairDesc pd = pairs[t.pair];
+    float *X = xs[pd.worker] + pd.x_off;
+    if (pd.V == 4) row_body<4, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw);
+    else if (pd.V == 2) row_body<2, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw);
+    else row_body<1, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw);
+}
+
 // ---------------------------------------------------------------------------------------
 // Column-owner kernel.  A lane owns V adjacent columns of X_i and runs down a block of rows;
 // `lg` lanes sit side by side, the other lanes of the wavefront (and the other wavefronts)
-// take interleaved rows of the same columns and are summed at the end.
+// take interleaved rows of the same columns and are summed at the end.  The block's Phat
+// entries are staged in LDS once; the loads of the next U rows are issued before the
+// arithmetic of the current U rows.
 //   Qw[blk][j][c] = sum_{row in blk} X[row, c] * Phat_j[row]   (Algorithm 2, even iteration:
 //   the product with X^T, for every incident edge in one read of X_i)
 // ---------------------------------------------------------------------------------------
 template <int V, int RC, int U>
-__global__ void __launch_bounds__(kThreads)
-col_kernel(const ColTile *__restrict__ tiles, const PairDesc *__restrict__ pairs,
-           const ColDesc *__restrict__ cols, float *const *__restrict__ xs,
-           const float *__restrict__ phat, double *__restrict__ qw) {
-    __shared__ double red[kThreads / 64 - 1][64][V];
-    const ColTile t = tiles[blockIdx.x];
-    const PairDesc pd = pairs[t.pair];
-    const float *__restrict__ X = xs[pd.worker] + pd.x_off;
+__device__ __forceinline__ void col_body(const ColTile &t, const PairDesc &pd,
+                                         const ColDesc *__restrict__ cols, const float *X,
+                                         const float *__restrict__ phat, double *__restrict__ qw,
+                                         float *sT) {
+    typedef typename VecT<V>::T vec;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lg = pd.lg;
     const int lg_shift = __ffs(lg) - 1;
@@ -167,10 +256,15 @@ col_kernel(const ColTile *__restrict__ tiles, const PairDesc *__restrict__ pairs
     if (!cok) c = q - V;
     const int rb = t.blk * pd.blk_rows;
     const int re = min(pd.p, rb + pd.blk_rows);
+    const int nrows = re - rb;
 
-    const float *phc[RC];
-#pragma unroll
-    for (int j = 0; j < RC; ++j) phc[j] = phat + cols[pd.col0 + min(j, R - 1)].ph_off;
+    // stage Phat[rb:re, 0:R) as sT[row][j]; columns j >= R are zero
+    for (int idx = threadIdx.x; idx < nrows * RC; idx += kThreads) {
+        const int j = idx / nrows, rr = idx - j * nrows;
+        float v = 0.0f;
+        if (j < R) v = ldg1(phat + cols[pd.col0 + j].ph_off + rb + rr);
+        sT[rr * RC + j] = v;
+    }
 
     double acc[RC][V];
 #pragma unroll
@@ -178,25 +272,61 @@ col_kernel(const ColTile *__restrict__ tiles, const PairDesc *__restrict__ pairs
 #pragma unroll
         for (int v = 0; v < V; ++v) acc[j][v] = 0.0;
 
-    for (int row = rb + rg; row < re; row += RG * U) {
-        FV<V> xv[U];
-        float tv[U][RC];
+    const float *xcol = X + c;
+    auto load = [&](int row, vec(&xv)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int rr = min(row + u * RG, re - 1);
+            xv[u] = ldg<V>(xcol + (int64_t)rr * q);
+        }
+    };
+    auto process = [&](int row, vec(&xv)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int rr = row + u * RG;
             const bool ok = rr < re;
-            const int rc = ok ? rr : row;
-            xv[u] = ldv<V>(X + (int64_t)rc * q + c);
+            const int li = (min(rr, re - 1) - rb) * RC;
+            double xd[V];
 #pragma unroll
-            for (int j = 0; j < RC; ++j) tv[u][j] = ok ? phc[j][rc] : 0.0f;
+            for (int v = 0; v < V; ++v) xd[v] = (double)xv[u][v];
+#pragma unroll
+            for (int j = 0; j < RC; ++j) {
+                const float tf = sT[li + j];
+                const double td = ok ? (double)tf : 0.0;
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[j][v] = fma(xd[v], td, acc[j][v]);
+            }
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int j = 0; j < RC; ++j)
-#pragma unroll
-                for (int v = 0; v < V; ++v)
-                    acc[j][v] = fma((double)xv[u].a[v], (double)tv[u][j], acc[j][v]);
+    };
+
+    int row = rb + rg;
+    const int stride = RG * U;
+    vec xa[U], xb[U];
+    const bool active = row < re;
+    int rem = active ? (re - row - 1) / stride : 0;
+    if (active) load(row, xa);
+    __syncthreads();  // Phat staged
+    if (active) {
+        while (rem >= 2) {
+            load(row + stride, xb);
+            PG_FENCE();
+            process(row, xa);
+            PG_FENCE();
+            load(row + 2 * stride, xa);
+            PG_FENCE();
+            process(row + stride, xb);
+            PG_FENCE();
+            row += 2 * stride;
+            rem -= 2;
+        }
+        if (rem == 1) {
+            load(row + stride, xb);
+            PG_FENCE();
+            process(row, xa);
+            process(row + stride, xb);
+        } else {
+            process(row, xa);
+        }
     }
     // lanes of one wavefront that hold the same columns
     for (int o = lg; o < 64; o <<= 1)
@@ -204,7 +334,9 @@ col_kernel(const ColTile *__restrict__ tiles, const PairDesc *__restrict__ pairs
         for (int j = 0; j < RC; ++j)
 #pragma unroll
             for (int v = 0; v < V; ++v) acc[j][v] += __shfl_xor(acc[j][v], o);
-    // the four wavefronts, one stacked column at a time
+    // the four wavefronts, one stacked column at a time, through LDS
+    __syncthreads();  // everyone is done with sT
+    double(*red)[64][V] = reinterpret_cast<double(*)[64][V]>(sT);
 #pragma unroll
     for (int j = 0; j < RC; ++j) {
         if (j < R) {
@@ -225,6 +357,22 @@ col_kernel(const ColTile *__restrict__ tiles, const PairDesc *__restrict__ pairs
             __syncthreads();
         }
     }
+}
+
+template <int RC, int U>
+__global__ void __launch_bounds__(kThreads)
+col_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
+           const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
+           float *const *__restrict__ xs, const float *__restrict__ phat,
+           double *__restrict__ qw) {
+    extern __shared__ double smem[];  // [blk_rows][RC] Phat floats, then reused for the reduction
+    float *sT = reinterpret_cast<float *>(smem);
+    const ColTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
+    const PairDesc pd = pairs[t.pair];
+    const float *X = xs[pd.worker] + pd.x_off;
+    if (pd.V == 4) col_body<4, RC, U>(t, pd, cols, X, phat, qw, sT);
+    else if (pd.V == 2) col_body<2, RC, U>(t, pd, cols, X, phat, qw, sT);
+    else col_body<1, RC, U>(t, pd, cols, X, phat, qw, sT);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -110,7 +110,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         int lg, nblk, blk_rows;                  // column-owner
     };
     std::vector<Geo> geo(n_layers);
-    constexpr int kColUnroll = 4;
+    constexpr int kColUnroll = 8;
     for (int l = 0; l < n_layers; ++l) {
         const LayerInfo &L = P.layers[l];
         Geo &g = geo[l];
@@ -122,14 +122,14 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         // blocking depends on the stacked column count; size for the best-connected worker.
         size_t max_deg = 0;
         for (int i = 0; i < n_workers; ++i) max_deg = std::max(max_deg, P.incident[i].size());
-        int rows_iter = 4 * (64 / g.lpr) * rows_unroll(compiled_cols(std::max<int>(1, (int)max_deg * L.r)));
+        int rows_iter = (64 / g.lpr) * rows_unroll(compiled_cols(std::max<int>(1, (int)max_deg * L.r)));
         int64_t chunk_bytes = (int64_t)rows_iter * chunk * 4;
         int seg_chunks = (int)std::max<int64_t>(1, tune.row_tile_bytes / chunk_bytes);
         g.nseg = (nchunks + seg_chunks - 1) / seg_chunks;
         seg_chunks = (nchunks + g.nseg - 1) / g.nseg;
         g.nseg = (nchunks + seg_chunks - 1) / seg_chunks;
         g.seg_len = seg_chunks * chunk;
-        g.rows_iter_base = 4 * (64 / g.lpr);
+        g.rows_iter_base = 64 / g.lpr;  // one wavefront per tile
 
         // Column-owner kernel: lanes side by side over columns; pick the lane-group width that
         // wastes the fewest lanes on the ragged end of a row (ties go to the wider group).
@@ -178,7 +178,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             pd.lg = g.lg;
             pd.nblk = g.nblk;
             pd.blk_rows = g.blk_rows;
-            pd.pad = 0;
+            pd.V = L.V;
             pwo += (int64_t)g.nseg * pd.R * L.p;
             qwo += (int64_t)g.nblk * pd.R * L.q;
             for (int e : P.incident[i])
@@ -249,31 +249,21 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     o = (size_t)round_up(o + (size_t)flo * 4, 256);
     P.ws_bytes = std::max<size_t>(o, 256);
 
-    // ---- tiles, grouped by kernel instantiation, heaviest first ----
+    // ---- tiles, grouped by kernel instantiation, in address order ----
     P.row_classes.clear();
     P.col_classes.clear();
-    auto row_class = [&](int V, int RC) -> RowClass & {
-        for (auto &c : P.row_classes)
-            if (c.V == V && c.RC == RC) return c;
-        P.row_classes.push_back({V, RC, {}, 0, 0});
-        return P.row_classes.back();
+    auto row_class = [&](int RC) -> size_t {
+        for (size_t k = 0; k < P.row_classes.size(); ++k)
+            if (P.row_classes[k].RC == RC) return k;
+        P.row_classes.push_back({RC, {}, 0, 0});
+        return P.row_classes.size() - 1;
     };
-    auto col_class = [&](int V, int RC) -> ColClass & {
-        for (auto &c : P.col_classes)
-            if (c.V == V && c.RC == RC) return c;
-        P.col_classes.push_back({V, RC, {}, 0, 0});
-        return P.col_classes.back();
+    auto col_class = [&](int RC) -> size_t {
+        for (size_t k = 0; k < P.col_classes.size(); ++k)
+            if (P.col_classes[k].RC == RC) return k;
+        P.col_classes.push_back({RC, {}, 0, 0, 0});
+        return P.col_classes.size() - 1;
     };
-    struct Weighted {
-        int64_t w;
-        RowTile t;
-    };
-    struct WeightedC {
-        int64_t w;
-        ColTile t;
-    };
-    std::vector<std::vector<Weighted>> rtmp;
-    std::vector<std::vector<WeightedC>> ctmp;
     for (int l = 0; l < n_layers; ++l) {
         const LayerInfo &L = P.layers[l];
         const Geo &g = geo[l];
@@ -282,9 +272,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             const PairDesc &pd = P.pairs[pair];
             if (pd.R == 0) continue;  // isolated worker: nothing to multiply or update
             int RC = compiled_cols(pd.R);
-            RowClass &rc = row_class(L.V, RC);
-            size_t rci = &rc - &P.row_classes[0];
-            if (rtmp.size() <= rci) rtmp.resize(rci + 1);
+            RowClass &rc = P.row_classes[row_class(RC)];
             int rows_iter = g.rows_iter_base * rows_unroll(RC);
             int iters = 1;
             if (g.nseg == 1) {
@@ -293,35 +281,17 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             }
             int tile_rows = rows_iter * iters;
             for (int r0 = 0; r0 < L.p; r0 += tile_rows)
-                for (int s = 0; s < g.nseg; ++s) {
-                    int nr = std::min(tile_rows, L.p - r0);
-                    int len = std::min(g.seg_len, L.q - s * g.seg_len);
-                    rtmp[rci].push_back({(int64_t)nr * len, {pair, r0, nr, s}});
-                }
+                for (int sg = 0; sg < g.nseg; ++sg)
+                    rc.tiles.push_back({pair, r0, std::min(tile_rows, L.p - r0), sg});
             rc.elems += (double)L.p * L.q;
 
-            ColClass &cc = col_class(L.V, RC);
-            size_t cci = &cc - &P.col_classes[0];
-            if (ctmp.size() <= cci) ctmp.resize(cci + 1);
+            ColClass &cc = P.col_classes[col_class(RC)];
             int cw = g.lg * L.V;
             for (int b = 0; b < g.nblk; ++b)
-                for (int c0 = 0; c0 < L.q; c0 += cw) {
-                    int nr = std::min(g.blk_rows, L.p - b * g.blk_rows);
-                    int len = std::min(cw, L.q - c0);
-                    ctmp[cci].push_back({(int64_t)nr * len, {pair, c0, b, 0}});
-                }
+                for (int c0 = 0; c0 < L.q; c0 += cw) cc.tiles.push_back({pair, c0, b, 0});
             cc.elems += (double)L.p * L.q;
+            cc.max_rows = std::max(cc.max_rows, g.blk_rows);
         }
-    }
-    for (size_t k = 0; k < P.row_classes.size(); ++k) {
-        std::stable_sort(rtmp[k].begin(), rtmp[k].end(),
-                         [](const Weighted &x, const Weighted &y) { return x.w > y.w; });
-        for (auto &w : rtmp[k]) P.row_classes[k].tiles.push_back(w.t);
-    }
-    for (size_t k = 0; k < P.col_classes.size(); ++k) {
-        std::stable_sort(ctmp[k].begin(), ctmp[k].end(),
-                         [](const WeightedC &x, const WeightedC &y) { return x.w > y.w; });
-        for (auto &w : ctmp[k]) P.col_classes[k].tiles.push_back(w.t);
     }
     return PG_OK;
 }

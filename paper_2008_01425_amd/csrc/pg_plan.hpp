@@ -15,23 +15,25 @@ struct LayerInfo {
     int64_t x_off;      // float offset inside a worker buffer
 };
 
-// Tiles of one kernel instantiation: vector width V and compiled column count RC >= R.
+// Tiles of one kernel instantiation: compiled column count RC >= R.  Tiles keep the order
+// layer, worker, rows: the address order every pass walks (forwards or backwards).
 struct RowClass {
-    int V, RC;
+    int RC;
     std::vector<RowTile> tiles;
     size_t dev_first = 0;   // index of the first tile in the uploaded table
     double elems = 0;       // parameter elements covered (for byte accounting)
 };
 struct ColClass {
-    int V, RC;
+    int RC;
     std::vector<ColTile> tiles;
     size_t dev_first = 0;
     double elems = 0;
+    int max_rows = 0;       // largest row block (sizes the staged Phat slice in LDS)
 };
 
 struct Tuning {
-    int row_tile_bytes = 96 * 1024;  // target parameter bytes per row-owner tile
-    int col_tile_bytes = 128 * 1024; // target parameter bytes per column-owner tile
+    int row_tile_bytes = 72 * 1024;  // target parameter bytes per row-owner tile (one wavefront)
+    int col_tile_bytes = 512 * 1024; // target parameter bytes per column-owner tile (four wavefronts)
 };
 
 struct Plan {

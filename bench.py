@@ -20,6 +20,16 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 
+# Bytes that crossed the L2 -> fabric boundary per launch of a kernel kind, from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs of this script, each scaled by the same counter's reading for a plain
+# 512 MiB device copy (factors 2.000 and 1.000); see profiles/vgg16_r1_traffic_counters.txt.
+MEASURED_TRAFFIC_BYTES = {
+    ("vgg16_r1", "update_sweep_p"): 960.4e6 + 943.6e6,
+    ("vgg16_r1", "update"): 963.4e6 + 941.8e6,
+    ("vgg16_r1", "sweep_p"): 958.8e6 + 1.8e6,
+    ("vgg16_r1", "sweep_q"): 946.3e6 + 8.7e6,
+}
+
 
 def cpu_baseline(wl, seconds_budget: float):
     """Time the CPU oracle (as it stands, single-threaded) on the same workload."""
@@ -51,6 +61,9 @@ def main():
                     help="tiny | resnet20 | vgg16_r1 | vgg16_r2 | lstm | resnet50")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also run a plain device copy of this many MiB (known traffic, for scaling "
+                         "hardware byte counters in a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all simulated workers share its HBM); "
@@ -96,7 +109,8 @@ def main():
         for r in rows:
             gbs = r["bytes"] / (r["ms"] * 1e-3) / 1e9 if r["ms"] > 0 else 0.0
             out[r["name"]] = {"launches": r["launches"], "avg_ms": r["ms"] / max(1, r["launches"]),
-                              "total_ms": r["ms"], "GBps": gbs, "frac_of_peak": gbs / HBM_PEAK_GBS}
+                              "total_ms": r["ms"], "algorithmic_bytes_per_launch": r["bytes"] / max(1, r["launches"]),
+                              "GBps": gbs, "frac_of_peak": gbs / HBM_PEAK_GBS}
         return out
 
     Kp = min(K, 50)
@@ -106,7 +120,9 @@ def main():
     # the dominant kernel of the timed (fused) pipeline
     dom = max(k_fused.items(), key=lambda kv: kv[1]["total_ms"])
     roofline = {"bound": "hbm", "kernel": dom[0], "achieved": dom[1]["GBps"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": dom[1]["GBps"] / HBM_PEAK_GBS, "traffic": None,
+                "unit": "GB/s", "frac": dom[1]["GBps"] / HBM_PEAK_GBS,
+                "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom[0])),
+                "algorithmic_bytes_per_launch": dom[1]["algorithmic_bytes_per_launch"],
                 "avg_launch_ms": dom[1]["avg_ms"]}
 
     bytes_fused = B.pg_round_bytes(gb.ctx, True)
@@ -141,6 +157,15 @@ def main():
     gb.close()
     del gb
     torch.cuda.empty_cache()
+    if args.copy_calibration > 0:
+        n = args.copy_calibration * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        result["copy_calibration"] = {"MiB": args.copy_calibration, "bytes_read": 4 * n, "bytes_written": 4 * n}
+        del src, dst
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
     else:

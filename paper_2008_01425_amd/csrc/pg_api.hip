@@ -39,6 +39,7 @@ struct pg_ctx {
     float **d_xs = nullptr;
     std::vector<float *> xs_cached;
     bool profiling = false;
+    int col_reverse = 1;
     std::vector<ProfRec> recs;
     std::vector<hipEvent_t> free_events;
 };
@@ -172,7 +173,7 @@ struct Launcher {
             // LDS: the staged Phat slice, later reused for the cross-wavefront sums
             size_t lds = std::max((size_t)cc.max_rows * cc.RC * sizeof(float),
                                   (size_t)(kThreads / 64 - 1) * 64 * 4 * sizeof(double));
-#define PG_COL(RCV) col_kernel<RCV, U><<<grid, block, lds, st>>>(tiles, n, /*reverse=*/1, c->d_pairs, c->d_cols, c->d_xs, ph(), qw())
+#define PG_COL(RCV) col_kernel<RCV, U><<<grid, block, lds, st>>>(tiles, n, /*reverse=*/c->col_reverse, c->d_pairs, c->d_cols, c->d_xs, ph(), qw())
             switch (cc.RC) {
                 case 1: PG_COL(1); break;
                 case 2: PG_COL(2); break;
@@ -266,6 +267,7 @@ int pg_init(pg_ctx **out, int n_workers, int n_edges, const int32_t *edges, cons
     if (!c) return PG_ERR_NOMEM;
     Tuning tune;
     if (const char *e = getenv("PG_ROW_TILE_BYTES")) tune.row_tile_bytes = std::max(1024, atoi(e));
+    if (const char *e = getenv("PG_COL_REVERSE")) c->col_reverse = atoi(e) != 0;
     if (const char *e = getenv("PG_COL_TILE_BYTES")) tune.col_tile_bytes = std::max(1024, atoi(e));
     int rc;
     try {

@@ -1,0 +1,157 @@
+"""Host-side logic of the C-ABI library, without a GPU: the library loads, exports every
+symbol the header declares, validates its inputs and reports consistent layouts."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2008_01425_amd import binding as B
+from paper_2008_01425_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _init(n, edges, w, shapes, rank=1, steps=1):
+    edges = np.asarray(edges, dtype=np.int32).reshape(-1, 2)
+    ew = np.full((len(edges),), w, dtype=np.float32) if np.isscalar(w) else np.asarray(w, np.float32)
+    return B.pg_init(n, edges, ew, [s[0] for s in shapes], [s[1] for s in shapes], rank, steps)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "powergossip.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(pg_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    raw = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(raw, name), name
+
+
+def test_strerror_covers_all_codes():
+    texts = {B.pg_strerror(c) for c in (0, -1, -2, -3, -4, -5)}
+    assert len(texts) == 6 and all(texts)
+    assert "unknown" in B.pg_strerror(-99)
+
+
+@pytest.mark.parametrize("edges,code", [
+    ([[0, 0]], B.PG_ERR_TOPOLOGY),            # self-loop
+    ([[0, 3]], B.PG_ERR_TOPOLOGY),            # out of range
+    ([[-1, 1]], B.PG_ERR_TOPOLOGY),
+    ([[0, 1], [1, 0]], B.PG_ERR_TOPOLOGY),    # duplicate, reversed
+    ([[0, 1], [0, 1]], B.PG_ERR_TOPOLOGY),
+])
+def test_bad_topologies_are_rejected(edges, code):
+    with pytest.raises(B.PGError) as e:
+        _init(3, edges, 0.2, [(4, 4)])
+    assert e.value.status == code
+
+
+def test_bad_arguments_are_rejected():
+    ok_edges = [[0, 1], [1, 2]]
+    cases = [
+        (lambda: _init(3, ok_edges, 0.2, [(0, 4)]), B.PG_ERR_SHAPE),
+        (lambda: _init(3, ok_edges, 0.2, [(4, -1)]), B.PG_ERR_SHAPE),
+        (lambda: _init(3, ok_edges, 0.2, [(4, 4)], rank=0), B.PG_ERR_ARG),
+        (lambda: _init(3, ok_edges, 0.2, [(4, 4)], steps=0), B.PG_ERR_ARG),
+        (lambda: _init(0, [], 0.2, [(4, 4)]), B.PG_ERR_ARG),
+        (lambda: _init(3, ok_edges, -0.1, [(4, 4)]), B.PG_ERR_ARG),
+        (lambda: _init(3, ok_edges, float("nan"), [(4, 4)]), B.PG_ERR_ARG),
+        (lambda: _init(3, ok_edges, 0.6, [(4, 4)]), B.PG_ERR_ARG),      # worker 1: 1.2 > 1
+        (lambda: _init(3, ok_edges, 0.2, [(64, 64)], rank=9), B.PG_ERR_ARG),  # 2 edges * 9 > 16 columns
+    ]
+    for fn, code in cases:
+        with pytest.raises(B.PGError) as e:
+            fn()
+        assert e.value.status == code
+    assert B.lib.pg_init(None, 1, 0, None, None, 1, None, None, 1, 1) == B.PG_ERR_ARG
+    assert B.lib.pg_destroy(None) == B.PG_ERR_ARG
+    assert B.lib.pg_round(None, None, None, None, None) == B.PG_ERR_ARG
+
+
+def test_layouts_are_aligned_disjoint_and_complete():
+    wl = W.get("resnet20")
+    ctx = _init(wl.n_workers, wl.edges, wl.edge_w, wl.shapes, rank=2, steps=1)
+    L, E = len(wl.shapes), wl.n_edges
+    spans = []
+    for l, (p, q) in enumerate(wl.shapes):
+        off = B.pg_layer_offset(ctx, l)
+        assert off % 4 == 0
+        assert B.pg_layer_rank(ctx, l) == min(2, p, q)
+        spans.append((off, off + p * q))
+    spans.sort()
+    assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
+    assert spans[-1][1] <= B.pg_param_floats(ctx) < spans[-1][1] + 4
+    qsp = []
+    for e in range(E):
+        for l, (p, q) in enumerate(wl.shapes):
+            off = B.pg_q_offset(ctx, e, l)
+            assert off % 4 == 0
+            qsp.append((off, off + q * min(2, p, q)))
+    qsp.sort()
+    assert all(a[1] <= b[0] for a, b in zip(qsp, qsp[1:]))
+    assert qsp[-1][1] <= B.pg_qstate_floats(ctx)
+    ws = B.pg_workspace_bytes(ctx)
+    assert ws % 256 == 0 and ws > 0
+    seen = []
+    for e in range(E):
+        for l, (p, q) in enumerate(wl.shapes):
+            r = min(2, p, q)
+            po, fo = B.pg_ws_phat_offset(ctx, e, l), B.pg_ws_flag_offset(ctx, e, l)
+            assert po % 4 == 0 and po + 4 * r * p <= ws and fo + 4 * r <= ws
+            seen.append((po, po + 4 * r * p))
+            seen.append((fo, fo + 4 * r))
+    seen.sort()
+    assert all(a[1] <= b[0] for a, b in zip(seen, seen[1:]))
+    # out-of-range queries
+    assert B.pg_layer_offset(ctx, L) == ctypes.c_size_t(-1).value
+    assert B.pg_q_offset(ctx, E, 0) == ctypes.c_size_t(-1).value
+    assert B.pg_layer_rank(ctx, -1) == -1
+    B.pg_destroy(ctx)
+
+
+@pytest.mark.parametrize("name,N,mats", [("tiny", 2576, 2), ("resnet20", 269722, 20),
+                                         ("vgg16_r1", 14715584, 14), ("lstm", 28390700, 5),
+                                         ("resnet50", 25557032, 54)])
+def test_workload_shapes_and_byte_accounting(name, N, mats):
+    wl = W.get(name)
+    assert wl.params_per_worker == N
+    assert sum(1 for p, q in wl.shapes if q > 1) == mats
+    ctx = _init(wl.n_workers, wl.edges, wl.edge_w, wl.shapes, wl.rank, wl.power_steps)
+    s = wl.power_steps
+    assert B.pg_round_bytes(ctx, False) == 4.0 * wl.n_workers * N * (2 * s + 2)
+    assert B.pg_round_bytes(ctx, True) == 4.0 * wl.n_workers * N * (2 * s + 1)
+    assert B.pg_message_floats(ctx) == sum(min(wl.rank, p, q) * (p + q) for p, q in wl.shapes)
+    B.pg_destroy(ctx)
+
+
+def test_message_floats_reproduce_the_papers_compression_column():
+    """One power step sends a length-p and a length-q vector per matrix (two of the paper's
+    iterations): p*q / (message/2) is the printed per-tensor ratio."""
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "compression_ratios.txt"))
+            if l.strip() and not l.startswith("#")]
+    for p, q, printed in [(int(a), int(b), int(c)) for a, b, c in rows]:
+        ctx = _init(2, [[0, 1]], 0.5, [(p, q)])
+        assert round(p * q / (B.pg_message_floats(ctx) / 2)) == printed
+        B.pg_destroy(ctx)
+
+
+def test_topology_builders():
+    assert W.ring_edges(4).tolist() == [[0, 1], [1, 2], [2, 3], [3, 0]]
+    t = W.torus_edges(4, 4)
+    assert t.shape == (32, 2)
+    deg = np.bincount(t.reshape(-1), minlength=16)
+    assert (deg == 4).all()
+    assert len({tuple(sorted(e)) for e in t.tolist()}) == 32
+
+
+def test_seeded_blocks_are_reproducible_and_independent():
+    wl = W.get("tiny")
+    a = wl.worker_layer(2, 1)
+    assert np.array_equal(a, W.get("tiny").worker_layer(2, 1))
+    assert not np.array_equal(a, wl.worker_layer(3, 1))
+    d = (wl.worker_layer(0, 0).astype(np.float64) - wl.base(0))
+    assert abs(d.std() - 0.1) < 0.01
+    q = wl.q_init(1, 0)
+    assert q.shape == (1, 32) and abs(q.std() - 1.0) < 0.3

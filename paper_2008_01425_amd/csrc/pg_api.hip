@@ -15,6 +15,8 @@ using namespace pg;
 
 namespace {
 
+constexpr int kOrthThreads = 1024;
+
 enum Kind { K_SWEEP_P = 0, K_ORTH_P, K_SWEEP_Q, K_COMBINE_Q, K_UPDATE, K_UPDATE_SWEEP_P, K_COUNT };
 const char *const kKindName[K_COUNT] = {"sweep_p", "orth_p",  "sweep_q",
                                         "combine_q", "update", "update_sweep_p"};
@@ -128,17 +130,36 @@ struct Launcher {
 
     template <int RC, bool UPD, bool SWP>
     void row_launch(const RowClass &rc) {
-        constexpr int M = (RC <= 2) ? 8 : (RC <= 4 ? 4 : (RC <= 8 ? 2 : 1));
         const int n = (int)rc.tiles.size();
-        row_kernel<RC, M, UPD, SWP><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
-            c->d_row_tiles + rc.dev_first, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, qstate,
-            ph(), pw());
+        const RowTile *tiles = c->d_row_tiles + rc.dev_first;
+        if constexpr (RC < kWideCols) {
+            constexpr int M = (RC <= 2) ? 8 : 4;
+            row_kernel<RC, M, UPD, SWP><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
+                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, qstate, ph(), pw());
+        } else {
+            // register budget: RC accumulators and RC update coefficients per row
+            constexpr int M = 4;
+            size_t lds = (size_t)RC * rc.max_seg * sizeof(float);
+            row_wide_kernel<RC, M, UPD, SWP><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>(
+                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, qstate, ph(), pw());
+        }
     }
     template <int RC>
     void row_mode(const RowClass &rc, bool upd, bool swp) {
-        if (upd && swp) row_launch<RC, true, true>(rc);
-        else if (upd) row_launch<RC, true, false>(rc);
-        else row_launch<RC, false, true>(rc);
+        if (upd && swp) {
+            if constexpr (RC < kWideCols) {
+                row_launch<RC, true, true>(rc);
+            } else {
+                // with many stacked columns the fused pass does not fit in registers and is bound
+                // by arithmetic, not memory: two passes are faster
+                row_launch<RC, true, false>(rc);
+                row_launch<RC, false, true>(rc);
+            }
+        } else if (upd) {
+            row_launch<RC, true, false>(rc);
+        } else {
+            row_launch<RC, false, true>(rc);
+        }
     }
     // One pass of the row-owner kernels over every parameter, front to back: sweep, update, or both.
     void rows(bool upd, bool swp) {
@@ -161,27 +182,31 @@ struct Launcher {
 
     // The Q-sweep walks the parameters back to front: it starts on what the pass before it
     // (always a front-to-back row pass) touched last.
+    template <int RC>
+    void col_launch(const ColClass &cc) {
+        constexpr int U = (RC <= 2) ? 8 : 4;  // rows in flight per lane
+        const int n = (int)cc.tiles.size();
+        // LDS: the staged Phat slice plus one zero row, later reused for the cross-wavefront sums
+        size_t lds = std::max((size_t)(cc.max_rows + 1) * RC * sizeof(float),
+                              (size_t)(kThreads / 64 - 1) * 64 * 4 * sizeof(double));
+        col_kernel<RC, U><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>(
+            c->d_col_tiles + cc.dev_first, n, /*reverse=*/c->col_reverse, c->d_pairs, c->d_cols,
+            c->d_xs, ph(), qw());
+    }
+    // The Q-sweep walks the parameters back to front: it starts on what the pass before it
+    // (always a front-to-back row pass) touched last.
     void sweep_q() {
         if (status) return;
-        constexpr int U = 8;
         for (const ColClass &cc : c->plan.col_classes) {
             if (cc.tiles.empty()) continue;
             begin(K_SWEEP_Q, cc.elems * 4.0);
-            const int n = (int)cc.tiles.size();
-            dim3 grid((unsigned)n), block(kThreads);
-            const ColTile *tiles = c->d_col_tiles + cc.dev_first;
-            // LDS: the staged Phat slice, later reused for the cross-wavefront sums
-            size_t lds = std::max((size_t)cc.max_rows * cc.RC * sizeof(float),
-                                  (size_t)(kThreads / 64 - 1) * 64 * 4 * sizeof(double));
-#define PG_COL(RCV) col_kernel<RCV, U><<<grid, block, lds, st>>>(tiles, n, /*reverse=*/c->col_reverse, c->d_pairs, c->d_cols, c->d_xs, ph(), qw())
             switch (cc.RC) {
-                case 1: PG_COL(1); break;
-                case 2: PG_COL(2); break;
-                case 4: PG_COL(4); break;
-                case 8: PG_COL(8); break;
-                default: PG_COL(16); break;
+                case 1: col_launch<1>(cc); break;
+                case 2: col_launch<2>(cc); break;
+                case 4: col_launch<4>(cc); break;
+                case 8: col_launch<8>(cc); break;
+                default: col_launch<16>(cc); break;
             }
-#undef PG_COL
             check();
             end();
         }
@@ -189,7 +214,7 @@ struct Launcher {
     void orth_p() {
         if (status || c->plan.els.empty()) return;
         begin(K_ORTH_P, 0.0);
-        orth_kernel<256><<<dim3((unsigned)c->plan.els.size()), dim3(256), 0, st>>>(c->d_els, pw(), pdb(), ph(), flags());
+        orth_kernel<kOrthThreads><<<dim3((unsigned)c->plan.els.size()), dim3(kOrthThreads), 0, st>>>(c->d_els, pw(), pdb(), ph(), flags());
         check();
         end();
     }

@@ -11,7 +11,9 @@ namespace pg {
 
 constexpr int kMaxCols = 16;   // largest R = deg(i) * r_l one pass supports
 constexpr int kThreads = 256;  // work-group size of the column-owner and combine kernels (4 wavefronts)
-constexpr int kRowThreads = 64;  // row-owner kernels: one wavefront per tile
+constexpr int kRowThreads = 64;  // narrow row-owner kernels: one wavefront per tile
+constexpr int kWideCols = 8;     // from this many compiled columns on, row tiles stage Q in LDS
+constexpr int kWideLdsBytes = 48 * 1024;  // LDS budget of a wide row tile's Q slice
 
 // One stacked column of a (worker, layer) pair.
 struct ColDesc {

@@ -65,10 +65,40 @@ __device__ __forceinline__ double group_sum(double v, int width) {
     return v;
 }
 
+// The same for N values at once, exchange step outermost (one branch per step, not per value).
+template <int N>
+__device__ __forceinline__ void group_sum_all(double (&v)[N], int width) {
+    if (width > 1) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += dpp_mov<0xB1>(v[i]);
+    }
+    if (width > 2) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += dpp_mov<0x4E>(v[i]);
+    }
+    if (width > 4) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += dpp_mov<0x141>(v[i]);
+    }
+    if (width > 8) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += dpp_mov<0x140>(v[i]);
+    }
+    if (width > 16) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += swizzle_xor16(v[i]);
+    }
+    if (width > 32) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += __shfl_xor(v[i], 32);
+    }
+}
+
 // ---------------------------------------------------------------------------------------
-// Row-owner kernel: one wavefront per tile.  A group of `lpr` lanes walks along M rows of X_i
-// at once with vector loads; per column step it holds the RC stacked right-hand-side columns
-// for its slice.  The loads of step c + 1 are issued before the arithmetic of step c.
+// Row-owner kernel for few stacked columns (RC <= 4): one wavefront per tile.  A group of `lpr`
+// lanes walks along M rows of X_i at once with vector loads; per column step it holds the RC
+// stacked right-hand-side columns for its slice in registers (they come from L1/L2).  The
+// loads of step c + 1 are issued before the arithmetic of step c.
 //   SWEEP : Pw[j][row] = sum_c X[row, c] * Q_j[c]            (Algorithm 2, odd iteration:
 //           p_i = X_i v for every incident edge's v in one read of X_i)
 //   UPDATE: X[row, c] -= sum_j coef_j * Phat_j[row] * Q'_j[c] (Eq. (2) summed over the edges)
@@ -128,22 +158,13 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
 #pragma unroll
             for (int j = 0; j < RC; ++j) acc[m][j] = 0.0;
 
-        // Many stacked columns: only X is prefetched a step ahead, the (cache-resident) Q slice
-        // is fetched at the point of use, so that one Q buffer fits in registers.
-        constexpr bool QPF = RC <= 4;
         auto load = [&](int c, vec(&xv)[M], vec(&qv)[RC]) {
-            if (QPF) {
 #pragma unroll
-                for (int j = 0; j < RC; ++j) qv[j] = ldg<V>(qcol[j] + c);
-            }
+            for (int j = 0; j < RC; ++j) qv[j] = ldg<V>(qcol[j] + c);
 #pragma unroll
             for (int m = 0; m < M; ++m) xv[m] = ldg<V>(xrow[m] + c);
         };
         auto process = [&](int c, vec(&xv)[M], vec(&qv)[RC]) {
-            if (!QPF) {
-#pragma unroll
-                for (int j = 0; j < RC; ++j) qv[j] = ldg<V>(qcol[j] + c);
-            }
             double qd[RC][V];
 #pragma unroll
             for (int j = 0; j < RC; ++j)
@@ -201,14 +222,16 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
             }
         }
         if (SWEEP) {
+            double(&flat)[M * RC] = reinterpret_cast<double(&)[M * RC]>(acc);
+            group_sum_all<M * RC>(flat, lpr);
+            if (sub == 0) {
 #pragma unroll
-            for (int m = 0; m < M; ++m)
+                for (int m = 0; m < M; ++m)
 #pragma unroll
-                for (int j = 0; j < RC; ++j) {
-                    double s = group_sum(acc[m][j], lpr);
-                    if (sub == 0 && ok[m] && j < R)
-                        pw[pd.pw_off + ((int64_t)t.seg * R + j) * pd.p + rowi[m]] = s;
-                }
+                    for (int j = 0; j < RC; ++j)
+                        if (ok[m] && j < R)
+                            pw[pd.pw_off + ((int64_t)t.seg * R + j) * pd.p + rowi[m]] = acc[m][j];
+            }
         }
     }
 }
@@ -227,6 +250,178 @@ row_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
     if (pd.V == 4) row_body<4, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw);
     else if (pd.V == 2) row_body<2, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw);
     else row_body<1, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw);
+}
+
+// ---------------------------------------------------------------------------------------
+// Row-owner kernel for many stacked columns (RC >= 8): four wavefronts per tile share the
+// tile's Q slice, staged once in LDS (RC x segment floats), so each loaded X value meets all
+// RC columns without the Q slice being re-fetched per row.  Lane groups own M rows each as in
+// the narrow kernel; only X is prefetched a step ahead, in registers.
+// ---------------------------------------------------------------------------------------
+template <int V, int RC, int M, bool UPDATE, bool SWEEP>
+__device__ __forceinline__ void row_wide_body(const RowTile &t, const PairDesc &pd,
+                                              const ColDesc *__restrict__ cols, float *X,
+                                              const float *__restrict__ qstate,
+                                              const float *__restrict__ phat,
+                                              double *__restrict__ pw, float *sQ) {
+    typedef typename VecT<V>::T vec;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lpr = pd.lpr;
+    const int lpr_shift = __ffs(lpr) - 1;
+    const int sub = lane & (lpr - 1);
+    const int grp = wave * (64 >> lpr_shift) + (lane >> lpr_shift);
+    const int ngrp = (kThreads / 64) * (64 >> lpr_shift);
+    const int q = pd.q, R = pd.R;
+    const int c_begin = t.seg * pd.seg_len;
+    const int c_end = min(q, c_begin + pd.seg_len);
+    const int seg_cols = c_end - c_begin;
+    const int sstride = pd.seg_len;  // multiple of lpr * V: every column slice starts V-aligned
+    const int row_end = t.row0 + t.nrows;
+    const int step = lpr * V;
+
+    // stage Q[c_begin:c_end, 0:R) as sQ[j][c]; unused columns j >= R read as zero
+#pragma unroll 1
+    for (int j = 0; j < RC; ++j) {
+        if (j < R) {
+            const float *src = qstate + cols[pd.col0 + j].q_off + c_begin;
+            for (int cc = tid * V; cc < seg_cols; cc += kThreads * V)
+                *reinterpret_cast<vec *>(sQ + j * sstride + cc) = ldg<V>(src + cc);
+        } else {
+            vec z;
+#pragma unroll
+            for (int v = 0; v < V; ++v) z[v] = 0.0f;
+            for (int cc = tid * V; cc < seg_cols; cc += kThreads * V)
+                *reinterpret_cast<vec *>(sQ + j * sstride + cc) = z;
+        }
+    }
+    const float *phc[RC];
+    float coef[RC];
+    if (UPDATE) {
+#pragma unroll
+        for (int j = 0; j < RC; ++j) {
+            const ColDesc cd = cols[pd.col0 + min(j, R - 1)];
+            phc[j] = phat + cd.ph_off;
+            coef[j] = (j < R) ? cd.coef : 0.0f;
+        }
+    }
+    __syncthreads();
+
+    for (int rbase = t.row0 + grp * M; rbase < row_end; rbase += ngrp * M) {
+        float *xrow[M];
+        bool ok[M];
+        int rowi[M];
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            ok[m] = rbase + m < row_end;
+            rowi[m] = ok[m] ? rbase + m : row_end - 1;
+            xrow[m] = X + (int64_t)rowi[m] * q;
+        }
+        double cp[M][RC];
+        if (UPDATE) {
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+#pragma unroll
+                for (int j = 0; j < RC; ++j)
+                    cp[m][j] = (double)coef[j] * (double)ldg1(phc[j] + rowi[m]);
+        }
+        double acc[M][RC];
+#pragma unroll
+        for (int m = 0; m < M; ++m)
+#pragma unroll
+            for (int j = 0; j < RC; ++j) acc[m][j] = 0.0;
+
+        auto load = [&](int c, vec(&xv)[M]) {
+#pragma unroll
+            for (int m = 0; m < M; ++m) xv[m] = ldg<V>(xrow[m] + c);
+        };
+        auto process = [&](int c, vec(&xv)[M]) {
+            const float *sq = sQ + (c - c_begin);
+            double xd[M][V];
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+#pragma unroll
+                for (int v = 0; v < V; ++v) xd[m][v] = (double)xv[m][v];
+            if (UPDATE) {
+#pragma unroll
+                for (int j = 0; j < RC; ++j) {
+                    const vec qv = *reinterpret_cast<const vec *>(sq + j * sstride);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        const double qd = (double)qv[v];
+#pragma unroll
+                        for (int m = 0; m < M; ++m) xd[m][v] = fma(-cp[m][j], qd, xd[m][v]);
+                    }
+                }
+#pragma unroll
+                for (int m = 0; m < M; ++m) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        xv[m][v] = (float)xd[m][v];
+                        xd[m][v] = (double)xv[m][v];  // the sweep uses the stored (rounded) value
+                    }
+                    if (ok[m]) stg<V>(xrow[m] + c, xv[m]);
+                }
+            }
+            if (SWEEP) {
+#pragma unroll
+                for (int j = 0; j < RC; ++j) {
+                    const vec qv = *reinterpret_cast<const vec *>(sq + j * sstride);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        const double qd = (double)qv[v];
+#pragma unroll
+                        for (int m = 0; m < M; ++m) acc[m][j] = fma(xd[m][v], qd, acc[m][j]);
+                    }
+                }
+            }
+        };
+
+        int c = c_begin + sub * V;
+        if (c < c_end) {
+            vec xa[M], xb[M];
+            int rem = (c_end - c - 1) / step;  // steps after the first one
+            load(c, xa);
+#pragma unroll 1
+            for (; rem > 0; --rem) {
+                load(c + step, xb);
+                PG_FENCE();
+                process(c, xa);
+                PG_FENCE();
+#pragma unroll
+                for (int m = 0; m < M; ++m) xa[m] = xb[m];
+                c += step;
+            }
+            process(c, xa);
+        }
+        if (SWEEP) {
+            double(&flat)[M * RC] = reinterpret_cast<double(&)[M * RC]>(acc);
+            group_sum_all<M * RC>(flat, lpr);
+            if (sub == 0) {
+#pragma unroll
+                for (int m = 0; m < M; ++m)
+#pragma unroll
+                    for (int j = 0; j < RC; ++j)
+                        if (ok[m] && j < R)
+                            pw[pd.pw_off + ((int64_t)t.seg * R + j) * pd.p + rowi[m]] = acc[m][j];
+            }
+        }
+    }
+}
+
+template <int RC, int M, bool UPDATE, bool SWEEP>
+__global__ void __launch_bounds__(kThreads)
+row_wide_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
+                const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
+                float *const *__restrict__ xs, const float *__restrict__ qstate,
+                const float *__restrict__ phat, double *__restrict__ pw) {
+    extern __shared__ double smem[];
+    float *sQ = reinterpret_cast<float *>(smem);
+    const RowTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
+    const PairDesc pd = pairs[t.pair];
+    float *X = xs[pd.worker] + pd.x_off;
+    if (pd.V == 4) row_wide_body<4, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw, sQ);
+    else if (pd.V == 2) row_wide_body<2, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw, sQ);
+    else row_wide_body<1, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw, sQ);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -258,12 +453,13 @@ __device__ __forceinline__ void col_body(const ColTile &t, const PairDesc &pd,
     const int re = min(pd.p, rb + pd.blk_rows);
     const int nrows = re - rb;
 
-    // stage Phat[rb:re, 0:R) as sT[row][j]; columns j >= R are zero
-    for (int idx = threadIdx.x; idx < nrows * RC; idx += kThreads) {
-        const int j = idx / nrows, rr = idx - j * nrows;
-        float v = 0.0f;
-        if (j < R) v = ldg1(phat + cols[pd.col0 + j].ph_off + rb + rr);
-        sT[rr * RC + j] = v;
+    // stage Phat[rb:re, 0:R) as sT[row][j]; columns j >= R and the extra row `nrows` are zero
+    // (rows past the block's end are pointed at that zero row)
+#pragma unroll 1
+    for (int j = 0; j < RC; ++j) {
+        const float *src = (j < R) ? phat + cols[pd.col0 + j].ph_off + rb : nullptr;
+        for (int rr = threadIdx.x; rr <= nrows; rr += kThreads)
+            sT[rr * RC + j] = (j < R && rr < nrows) ? ldg1(src + rr) : 0.0f;
     }
 
     double acc[RC][V];
@@ -283,16 +479,13 @@ __device__ __forceinline__ void col_body(const ColTile &t, const PairDesc &pd,
     auto process = [&](int row, vec(&xv)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int rr = row + u * RG;
-            const bool ok = rr < re;
-            const int li = (min(rr, re - 1) - rb) * RC;
+            const int li = (min(row + u * RG, re) - rb) * RC;
             double xd[V];
 #pragma unroll
             for (int v = 0; v < V; ++v) xd[v] = (double)xv[u][v];
 #pragma unroll
             for (int j = 0; j < RC; ++j) {
-                const float tf = sT[li + j];
-                const double td = ok ? (double)tf : 0.0;
+                const double td = (double)sT[li + j];
 #pragma unroll
                 for (int v = 0; v < V; ++v) acc[j][v] = fma(xd[v], td, acc[j][v]);
             }
@@ -307,26 +500,17 @@ __device__ __forceinline__ void col_body(const ColTile &t, const PairDesc &pd,
     if (active) load(row, xa);
     __syncthreads();  // Phat staged
     if (active) {
-        while (rem >= 2) {
+#pragma unroll 1
+        for (; rem > 0; --rem) {
             load(row + stride, xb);
             PG_FENCE();
             process(row, xa);
             PG_FENCE();
-            load(row + 2 * stride, xa);
-            PG_FENCE();
-            process(row + stride, xb);
-            PG_FENCE();
-            row += 2 * stride;
-            rem -= 2;
+#pragma unroll
+            for (int u = 0; u < U; ++u) xa[u] = xb[u];
+            row += stride;
         }
-        if (rem == 1) {
-            load(row + stride, xb);
-            PG_FENCE();
-            process(row, xa);
-            process(row + stride, xb);
-        } else {
-            process(row, xa);
-        }
+        process(row, xa);
     }
     // lanes of one wavefront that hold the same columns
     for (int o = lg; o < 64; o <<= 1)

@@ -24,8 +24,7 @@ int compiled_cols(int R) {
 
 int rows_unroll(int RC) {
     if (RC <= 2) return 8;
-    if (RC <= 4) return 4;
-    return 2;
+    return 4;
 }
 
 int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const float *edge_w,
@@ -107,6 +106,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     // ---- per-layer launch geometry ----
     struct Geo {
         int lpr, nseg, seg_len, rows_iter_base;  // row-owner
+        bool wide;                               // row-owner: many stacked columns, Q slice in LDS
         int lg, nblk, blk_rows;                  // column-owner
     };
     std::vector<Geo> geo(n_layers);
@@ -115,21 +115,33 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         const LayerInfo &L = P.layers[l];
         Geo &g = geo[l];
         int nv = L.q / L.V;  // vector loads per row
-        g.lpr = std::min(64, pow2_ceil(nv));
-        int chunk = g.lpr * L.V;  // floats one lane group covers per step
-        int nchunks = (L.q + chunk - 1) / chunk;
-        // Column segments keep a tile near the byte target when a single row is long.  The row
-        // blocking depends on the stacked column count; size for the best-connected worker.
+        // The row blocking depends on the stacked column count; size for the best-connected worker.
         size_t max_deg = 0;
         for (int i = 0; i < n_workers; ++i) max_deg = std::max(max_deg, P.incident[i].size());
-        int rows_iter = (64 / g.lpr) * rows_unroll(compiled_cols(std::max<int>(1, (int)max_deg * L.r)));
-        int64_t chunk_bytes = (int64_t)rows_iter * chunk * 4;
-        int seg_chunks = (int)std::max<int64_t>(1, tune.row_tile_bytes / chunk_bytes);
+        int rc_max = compiled_cols(std::max<int>(1, (int)max_deg * L.r));
+        g.wide = rc_max >= kWideCols;
+        // Lanes per row: a whole wavefront for few stacked columns; 16 for many, where the
+        // per-row lane reduction (RC values per row) would otherwise rival the products.
+        g.lpr = std::min(g.wide ? 16 : 64, pow2_ceil(nv));
+        int chunk = g.lpr * L.V;  // floats one lane group covers per step
+        int nchunks = (L.q + chunk - 1) / chunk;
+        int seg_chunks;
+        if (!g.wide) {
+            // one wavefront per tile: column segments keep a tile near the byte target when a
+            // single row is long
+            int rows_iter = (64 / g.lpr) * rows_unroll(rc_max);
+            int64_t chunk_bytes = (int64_t)rows_iter * chunk * 4;
+            seg_chunks = (int)std::max<int64_t>(1, tune.row_tile_bytes / chunk_bytes);
+            g.rows_iter_base = 64 / g.lpr;
+        } else {
+            // four wavefronts per tile share the Q slice in LDS: RC * seg_len floats must fit
+            seg_chunks = std::max(1, kWideLdsBytes / (rc_max * 4) / chunk);
+            g.rows_iter_base = (kThreads / 64) * (64 / g.lpr);
+        }
         g.nseg = (nchunks + seg_chunks - 1) / seg_chunks;
         seg_chunks = (nchunks + g.nseg - 1) / g.nseg;
         g.nseg = (nchunks + seg_chunks - 1) / seg_chunks;
         g.seg_len = seg_chunks * chunk;
-        g.rows_iter_base = 64 / g.lpr;  // one wavefront per tile
 
         // Column-owner kernel: lanes side by side over columns; pick the lane-group width that
         // wastes the fewest lanes on the ragged end of a row (ties go to the wider group).
@@ -255,7 +267,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     auto row_class = [&](int RC) -> size_t {
         for (size_t k = 0; k < P.row_classes.size(); ++k)
             if (P.row_classes[k].RC == RC) return k;
-        P.row_classes.push_back({RC, {}, 0, 0});
+        P.row_classes.push_back({RC, {}, 0, 0, 0});
         return P.row_classes.size() - 1;
     };
     auto col_class = [&](int RC) -> size_t {
@@ -274,12 +286,21 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             int RC = compiled_cols(pd.R);
             RowClass &rc = P.row_classes[row_class(RC)];
             int rows_iter = g.rows_iter_base * rows_unroll(RC);
-            int iters = 1;
-            if (g.nseg == 1) {
-                int64_t bytes_iter = (int64_t)rows_iter * L.q * 4;
-                iters = (int)std::max<int64_t>(1, tune.row_tile_bytes / bytes_iter);
+            int tile_rows;
+            if (RC < kWideCols) {
+                int iters = 1;
+                if (g.nseg == 1) {
+                    int64_t bytes_iter = (int64_t)rows_iter * L.q * 4;
+                    iters = (int)std::max<int64_t>(1, tune.row_tile_bytes / bytes_iter);
+                }
+                tile_rows = rows_iter * iters;
+            } else {
+                // enough rows that staging the Q slice (RC rows' worth of traffic) is amortised
+                int64_t seg_bytes = (int64_t)std::min(g.seg_len, L.q) * 4;
+                int64_t want = std::max<int64_t>(8 * RC, tune.wide_tile_bytes / seg_bytes);
+                tile_rows = (int)(round_up(want, rows_iter));
+                rc.max_seg = std::max(rc.max_seg, g.seg_len);
             }
-            int tile_rows = rows_iter * iters;
             for (int r0 = 0; r0 < L.p; r0 += tile_rows)
                 for (int sg = 0; sg < g.nseg; ++sg)
                     rc.tiles.push_back({pair, r0, std::min(tile_rows, L.p - r0), sg});

@@ -22,6 +22,7 @@ struct RowClass {
     std::vector<RowTile> tiles;
     size_t dev_first = 0;   // index of the first tile in the uploaded table
     double elems = 0;       // parameter elements covered (for byte accounting)
+    int max_seg = 0;        // RC >= kWideCols: longest column segment (sizes the Q slice in LDS)
 };
 struct ColClass {
     int RC;
@@ -34,6 +35,7 @@ struct ColClass {
 struct Tuning {
     int row_tile_bytes = 72 * 1024;  // target parameter bytes per row-owner tile (one wavefront)
     int col_tile_bytes = 512 * 1024; // target parameter bytes per column-owner tile (four wavefronts)
+    int wide_tile_bytes = 256 * 1024; // target parameter bytes per wide row-owner tile (four wavefronts)
 };
 
 struct Plan {

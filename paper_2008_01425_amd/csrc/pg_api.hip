@@ -184,7 +184,7 @@ struct Launcher {
     // (always a front-to-back row pass) touched last.
     template <int RC>
     void col_launch(const ColClass &cc) {
-        constexpr int U = (RC <= 2) ? 8 : 4;  // rows in flight per lane
+        constexpr int U = (RC <= 2) ? 8 : (RC <= 8 ? 4 : 2);  // rows in flight per lane
         const int n = (int)cc.tiles.size();
         // LDS: the staged Phat slice plus one zero row, later reused for the cross-wavefront sums
         size_t lds = std::max((size_t)(cc.max_rows + 1) * RC * sizeof(float),

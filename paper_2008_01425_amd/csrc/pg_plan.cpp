@@ -103,6 +103,17 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         }
     P.qstate_floats = (size_t)qo;
 
+    // ---- tile sizes: the byte targets suit workloads that fill the chip many times over; small
+    // parameter sets are cut finer so that every SIMD still gets a tile ----
+    Tuning tn = tune;
+    {
+        const double total_bytes = 4.0 * n_workers * P.elems_per_worker;
+        const double slots = 4096.0;  // 256 CUs x 4 SIMDs x a few wavefronts
+        tn.row_tile_bytes = (int)std::max(8.0 * 1024, std::min((double)tune.row_tile_bytes, total_bytes / slots));
+        tn.col_tile_bytes = (int)std::max(32.0 * 1024, std::min((double)tune.col_tile_bytes, 4.0 * total_bytes / slots));
+        tn.wide_tile_bytes = (int)std::max(32.0 * 1024, std::min((double)tune.wide_tile_bytes, 4.0 * total_bytes / slots));
+    }
+
     // ---- per-layer launch geometry ----
     struct Geo {
         int lpr, nseg, seg_len, rows_iter_base;  // row-owner
@@ -131,7 +142,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             // single row is long
             int rows_iter = (64 / g.lpr) * rows_unroll(rc_max);
             int64_t chunk_bytes = (int64_t)rows_iter * chunk * 4;
-            seg_chunks = (int)std::max<int64_t>(1, tune.row_tile_bytes / chunk_bytes);
+            seg_chunks = (int)std::max<int64_t>(1, tn.row_tile_bytes / chunk_bytes);
             g.rows_iter_base = 64 / g.lpr;
         } else {
             // four wavefronts per tile share the Q slice in LDS: RC * seg_len floats must fit
@@ -156,10 +167,14 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
                 best = lgc;
             }
         }
+        // With many stacked columns the kernel is bound by arithmetic and LDS reads of Phat, and
+        // one row per wavefront (all 64 lanes side by side) with shorter row blocks measures best.
+        const bool col_heavy = rc_max >= 16;
+        if (col_heavy && (double)nv / ((double)((nv + 63) / 64) * 64) > 0.6) best = std::min(64, pow2_ceil(nv));
         g.lg = best;
         int row_groups = 4 * (64 / g.lg);
         int64_t row_bytes = (int64_t)g.lg * L.V * 4;
-        int64_t want = std::max<int64_t>(1, tune.col_tile_bytes / row_bytes);
+        int64_t want = std::max<int64_t>(1, (col_heavy ? std::min(tn.col_tile_bytes, 128 * 1024) : tn.col_tile_bytes) / row_bytes);
         int64_t unit = (int64_t)row_groups * kColUnroll;
         int64_t br = round_up(want, unit);
         if (br >= L.p) br = L.p;
@@ -291,13 +306,13 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
                 int iters = 1;
                 if (g.nseg == 1) {
                     int64_t bytes_iter = (int64_t)rows_iter * L.q * 4;
-                    iters = (int)std::max<int64_t>(1, tune.row_tile_bytes / bytes_iter);
+                    iters = (int)std::max<int64_t>(1, tn.row_tile_bytes / bytes_iter);
                 }
                 tile_rows = rows_iter * iters;
             } else {
                 // enough rows that staging the Q slice (RC rows' worth of traffic) is amortised
                 int64_t seg_bytes = (int64_t)std::min(g.seg_len, L.q) * 4;
-                int64_t want = std::max<int64_t>(8 * RC, tune.wide_tile_bytes / seg_bytes);
+                int64_t want = std::max<int64_t>(8 * RC, tn.wide_tile_bytes / seg_bytes);
                 tile_rows = (int)(round_up(want, rows_iter));
                 rc.max_seg = std::max(rc.max_seg, g.seg_len);
             }

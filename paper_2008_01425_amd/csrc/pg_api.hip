@@ -38,6 +38,7 @@ struct pg_ctx {
     ColTile *d_col_tiles = nullptr;
     EdgeLayerDesc *d_els = nullptr;
     CombTile *d_comb = nullptr;
+    OrthTile *d_orth = nullptr;
     float **d_xs = nullptr;
     std::vector<float *> xs_cached;
     bool profiling = false;
@@ -85,6 +86,7 @@ int do_upload(pg_ctx *c) {
     if ((rc = upload_vec(&c->d_col_tiles, ct))) return rc;
     if ((rc = upload_vec(&c->d_els, P.els))) return rc;
     if ((rc = upload_vec(&c->d_comb, P.comb_tiles))) return rc;
+    if ((rc = upload_vec(&c->d_orth, P.orth_tiles))) return rc;
     PG_HIP(hipMalloc((void **)&c->d_xs, sizeof(float *) * (size_t)P.n));
     c->uploaded = true;
     return PG_OK;
@@ -102,6 +104,7 @@ struct Launcher {
     double *pdb() const { return (double *)(ws + c->plan.ws_pd); }
     float *ph() const { return (float *)(ws + c->plan.ws_ph); }
     int32_t *flags() const { return (int32_t *)(ws + c->plan.ws_flag); }
+    double *gpart() const { return (double *)(ws + c->plan.ws_gpart); }
 
     hipEvent_t get_event() {
         if (!c->free_events.empty()) {
@@ -184,7 +187,7 @@ struct Launcher {
     // (always a front-to-back row pass) touched last.
     template <int RC>
     void col_launch(const ColClass &cc) {
-        constexpr int U = (RC <= 2) ? 8 : (RC <= 8 ? 4 : 2);  // rows in flight per lane
+        constexpr int U = (RC <= 2) ? 8 : 4;  // rows in flight per lane
         const int n = (int)cc.tiles.size();
         // LDS: the staged Phat slice plus one zero row, later reused for the cross-wavefront sums
         size_t lds = std::max((size_t)(cc.max_rows + 1) * RC * sizeof(float),
@@ -211,10 +214,29 @@ struct Launcher {
             end();
         }
     }
+    template <int NT, int RMAX>
+    void orth_launch() {
+        const Plan &P = c->plan;
+        if (P.orth_tiles.empty()) {
+            orth_gram_kernel<NT, RMAX><<<dim3((unsigned)P.els.size()), dim3(NT), 0, st>>>(
+                c->d_els, pw(), ph(), flags());
+        } else {
+            dim3 grid((unsigned)P.orth_tiles.size());
+            orth_gram_part_kernel<NT, RMAX><<<grid, dim3(NT), 0, st>>>(c->d_orth, c->d_els, pw(), gpart());
+            orth_gram_apply_kernel<NT, RMAX><<<grid, dim3(NT), 0, st>>>(c->d_orth, c->d_els, pw(), gpart(),
+                                                                        ph(), flags());
+        }
+    }
     void orth_p() {
         if (status || c->plan.els.empty()) return;
         begin(K_ORTH_P, 0.0);
-        orth_kernel<kOrthThreads><<<dim3((unsigned)c->plan.els.size()), dim3(kOrthThreads), 0, st>>>(c->d_els, pw(), pdb(), ph(), flags());
+        const int rmax = c->plan.max_layer_rank;
+        if (rmax <= 1) orth_launch<kOrthThreads, 1>();
+        else if (rmax <= 2) orth_launch<kOrthThreads, 2>();
+        else if (rmax <= 4) orth_launch<kOrthThreads, 4>();
+        else if (rmax <= 8) orth_launch<512, 8>();
+        else orth_kernel<kOrthThreads><<<dim3((unsigned)c->plan.els.size()), dim3(kOrthThreads), 0, st>>>(
+            c->d_els, pw(), pdb(), ph(), flags());
         check();
         end();
     }
@@ -324,6 +346,7 @@ int pg_destroy(pg_ctx *c) {
         (void)hipFree(c->d_col_tiles);
         (void)hipFree(c->d_els);
         (void)hipFree(c->d_comb);
+        (void)hipFree(c->d_orth);
         (void)hipFree(c->d_xs);
     }
     delete c;

@@ -64,6 +64,13 @@ struct EdgeLayerDesc {
     int64_t flag_off;          // int32 index of the r dropped-column flags
 };
 
+// Row chunk of one (edge, layer) for the two-kernel orthonormalisation of tall layers; the
+// chunks of an (edge, layer) are consecutive tiles.
+struct OrthTile {
+    int32_t el, row0, nrows, chunk, nchunks, pad;
+};
+constexpr int kOrthChunkRows = 4096;
+
 // combine_q tile: 256 consecutive elements of the r*q block of one (edge, layer).
 struct CombTile {
     int32_t el, first;

@@ -7,7 +7,7 @@
 // Two streaming kernel families cover the passes over X:
 //   row_kernel  -- a lane group owns rows: P-sweep (X S), rank-r update, or both fused;
 //   col_kernel  -- a lane owns columns:    Q-sweep (X^T T).
-// Two small kernels work per edge: orth_kernel (combine + Gram-Schmidt) and comb_kernel.
+// Small kernels work per edge: orth_gram_kernel / orth_kernel (combine + Gram-Schmidt) and comb_kernel.
 #include <hip/hip_runtime.h>
 #include <float.h>
 
@@ -626,6 +626,175 @@ orth_kernel(const EdgeLayerDesc *__restrict__ els, const double *__restrict__ pw
     }
 }
 
+// The same orthonormalisation for r <= RMAX <= 8 in two passes over P instead of O(r^2):
+// pass 1 forms the Gram matrix G = P^T P; one thread factors it, G = R^T R (R upper
+// triangular: R_jk is the Gram-Schmidt coefficient of column k on the orthonormal column j,
+// R_kk the norm of its residual, so the dropped-column test reads d_k = G_kk - sum_j R_jk^2
+// against max(FLT_MIN, 1e-10 G_kk)); pass 2 applies Phat = P R^-1 row by row by forward
+// substitution.  Same columns as the left-to-right Gram-Schmidt up to rounding in double.
+template <int RMAX>
+__device__ __forceinline__ void gram_load_row(const EdgeLayerDesc &d, const double *__restrict__ pw,
+                                              int row, double (&v)[RMAX]) {
+#pragma unroll
+    for (int k = 0; k < RMAX; ++k) {
+        double sa = 0.0, sb = 0.0;
+        if (k < d.r) {
+            for (int s = 0; s < d.nseg; ++s) {
+                sa += pw[d.pwa_off + s * d.pwa_seg + (int64_t)k * d.p + row];
+                sb += pw[d.pwb_off + s * d.pwb_seg + (int64_t)k * d.p + row];
+            }
+        }
+        v[k] = sa - sb;
+    }
+}
+
+// Pass 1 over rows [row0, row1): the work-group's Gram sums, packed G[j][k] (j <= k) at
+// k (k + 1) / 2 + j, left in sG.
+template <int NT, int RMAX>
+__device__ __forceinline__ void gram_rows(const EdgeLayerDesc &d, const double *__restrict__ pw,
+                                          int row0, int row1,
+                                          double (*sRed)[RMAX * (RMAX + 1) / 2], double *sG) {
+    constexpr int NG = RMAX * (RMAX + 1) / 2;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    double g[NG];
+#pragma unroll
+    for (int i = 0; i < NG; ++i) g[i] = 0.0;
+#pragma unroll 2
+    for (int row = row0 + tid; row < row1; row += NT) {
+        double v[RMAX];
+        gram_load_row<RMAX>(d, pw, row, v);
+        int idx = 0;
+#pragma unroll
+        for (int k = 0; k < RMAX; ++k)
+#pragma unroll
+            for (int j = 0; j <= k; ++j) {
+                g[idx] = fma(v[j], v[k], g[idx]);
+                ++idx;
+            }
+    }
+    group_sum_all<NG>(g, 64);
+    if (lane == 0) {
+#pragma unroll
+        for (int i = 0; i < NG; ++i) sRed[wave][i] = g[i];
+    }
+    __syncthreads();
+    if (tid < NG) {
+        double s = 0.0;
+        for (int w = 0; w < NT / 64; ++w) s += sRed[w][tid];
+        sG[tid] = s;
+    }
+    __syncthreads();
+}
+
+// One thread factors G = R^T R with the dropped-column rule; everyone waits for it.
+template <int RMAX>
+__device__ __forceinline__ void gram_factor(const EdgeLayerDesc &d, const double *G,
+                                            double (*sR)[RMAX], int *sDrop,
+                                            int32_t *__restrict__ flags, bool write_flags) {
+    if (threadIdx.x == 0) {
+        for (int k = 0; k < d.r; ++k) {
+            const double gkk = G[k * (k + 1) / 2 + k];
+            double dk = gkk;
+            for (int j = 0; j < k; ++j) {
+                double rjk = 0.0;
+                if (!sDrop[j]) {
+                    double t = G[k * (k + 1) / 2 + j];
+                    for (int i = 0; i < j; ++i)
+                        if (!sDrop[i]) t -= sR[i][j] * sR[i][k];
+                    rjk = t / sR[j][j];
+                }
+                sR[j][k] = rjk;
+                dk -= rjk * rjk;
+            }
+            double floor2 = 1e-10 * gkk;
+            if (floor2 < (double)FLT_MIN) floor2 = (double)FLT_MIN;
+            const int dropped = !(dk >= floor2);
+            sDrop[k] = dropped;
+            sR[k][k] = dropped ? 1.0 : sqrt(dk);
+            if (write_flags) flags[d.flag_off + k] = dropped;
+        }
+    }
+    __syncthreads();
+}
+
+// Pass 2 over rows [row0, row1): Phat = P R^-1 by forward substitution, rounded to float.
+template <int NT, int RMAX>
+__device__ __forceinline__ void gram_apply_rows(const EdgeLayerDesc &d, const double *__restrict__ pw,
+                                                float *__restrict__ phat, int row0, int row1,
+                                                const double (*sR)[RMAX], const int *sDrop) {
+#pragma unroll 2
+    for (int row = row0 + (int)threadIdx.x; row < row1; row += NT) {
+        double v[RMAX], ph[RMAX];
+        gram_load_row<RMAX>(d, pw, row, v);
+#pragma unroll
+        for (int k = 0; k < RMAX; ++k) {
+            if (k < d.r) {
+                double t = v[k];
+#pragma unroll
+                for (int j = 0; j < k; ++j) t -= sR[j][k] * ph[j];
+                ph[k] = sDrop[k] ? 0.0 : t / sR[k][k];
+                phat[d.ph_off + (int64_t)k * d.p + row] = (float)ph[k];
+            } else {
+                ph[k] = 0.0;
+            }
+        }
+    }
+}
+
+// Whole (edge, layer) in one work-group: used when every layer has few rows.
+template <int NT, int RMAX>
+__global__ void __launch_bounds__(NT)
+orth_gram_kernel(const EdgeLayerDesc *__restrict__ els, const double *__restrict__ pw,
+                 float *__restrict__ phat, int32_t *__restrict__ flags) {
+    constexpr int NG = RMAX * (RMAX + 1) / 2;
+    __shared__ double sRed[NT / 64][NG];
+    __shared__ double sG[NG];
+    __shared__ double sR[RMAX][RMAX];
+    __shared__ int sDrop[RMAX];
+    const EdgeLayerDesc d = els[blockIdx.x];
+    gram_rows<NT, RMAX>(d, pw, 0, d.p, sRed, sG);
+    gram_factor<RMAX>(d, sG, sR, sDrop, flags, true);
+    gram_apply_rows<NT, RMAX>(d, pw, phat, 0, d.p, sR, sDrop);
+}
+
+// Tall layers: the rows of an (edge, layer) are cut into chunks, one work-group each.  The first
+// kernel leaves each chunk's Gram sums in gpart; the second adds an (edge, layer)'s chunks in
+// order, factors (every chunk redoes this tiny step) and applies R^-1 to its own rows.
+template <int NT, int RMAX>
+__global__ void __launch_bounds__(NT)
+orth_gram_part_kernel(const OrthTile *__restrict__ tiles, const EdgeLayerDesc *__restrict__ els,
+                      const double *__restrict__ pw, double *__restrict__ gpart) {
+    constexpr int NG = RMAX * (RMAX + 1) / 2;
+    __shared__ double sRed[NT / 64][NG];
+    __shared__ double sG[NG];
+    const OrthTile t = tiles[blockIdx.x];
+    const EdgeLayerDesc d = els[t.el];
+    gram_rows<NT, RMAX>(d, pw, t.row0, t.row0 + t.nrows, sRed, sG);
+    if (threadIdx.x < NG) gpart[(int64_t)blockIdx.x * NG + threadIdx.x] = sG[threadIdx.x];
+}
+
+template <int NT, int RMAX>
+__global__ void __launch_bounds__(NT)
+orth_gram_apply_kernel(const OrthTile *__restrict__ tiles, const EdgeLayerDesc *__restrict__ els,
+                       const double *__restrict__ pw, const double *__restrict__ gpart,
+                       float *__restrict__ phat, int32_t *__restrict__ flags) {
+    constexpr int NG = RMAX * (RMAX + 1) / 2;
+    __shared__ double sG[NG];
+    __shared__ double sR[RMAX][RMAX];
+    __shared__ int sDrop[RMAX];
+    const OrthTile t = tiles[blockIdx.x];
+    const EdgeLayerDesc d = els[t.el];
+    if (threadIdx.x < NG) {
+        double s = 0.0;
+        const int64_t first = (int64_t)blockIdx.x - t.chunk;  // chunk 0 of this (edge, layer)
+        for (int c = 0; c < t.nchunks; ++c) s += gpart[(first + c) * NG + threadIdx.x];
+        sG[threadIdx.x] = s;
+    }
+    __syncthreads();
+    gram_factor<RMAX>(d, sG, sR, sDrop, flags, t.chunk == 0);
+    gram_apply_rows<NT, RMAX>(d, pw, phat, t.row0, t.row0 + t.nrows, sR, sDrop);
+}
+
 // Per (edge, layer): Q' = (sum of worker a's row-block partials) - (worker b's), rounded to
 // float into the state buffer; the column of a dropped Phat keeps its old state.
 // (Algorithm 2: v_ij <- p_j - p_i, unnormalised.)
@@ -639,12 +808,21 @@ comb_kernel(const CombTile *__restrict__ tiles, const EdgeLayerDesc *__restrict_
     if (idx >= (int64_t)d.r * d.q) return;
     const int k = (int)(idx / d.q);
     if (flags[d.flag_off + k]) return;
-    double sa = 0.0, sb = 0.0;
-    for (int b = 0; b < d.nblk; ++b) {
-        sa += qw[d.qwa_off + b * d.qwa_blk + idx];
-        sb += qw[d.qwb_off + b * d.qwb_blk + idx];
+    // four interleaved running sums keep several loads in flight; the order is fixed
+    double sa[4] = {0.0, 0.0, 0.0, 0.0}, sb[4] = {0.0, 0.0, 0.0, 0.0};
+    int b = 0;
+    for (; b + 4 <= d.nblk; b += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            sa[u] += qw[d.qwa_off + (b + u) * d.qwa_blk + idx];
+            sb[u] += qw[d.qwb_off + (b + u) * d.qwb_blk + idx];
+        }
     }
-    qstate[d.q_off + idx] = (float)(sa - sb);
+    for (; b < d.nblk; ++b) {
+        sa[0] += qw[d.qwa_off + b * d.qwa_blk + idx];
+        sb[0] += qw[d.qwb_off + b * d.qwb_blk + idx];
+    }
+    qstate[d.q_off + idx] = (float)(((sa[0] + sa[1]) + (sa[2] + sa[3])) - ((sb[0] + sb[1]) + (sb[2] + sb[3])));
 }
 
 }  // namespace pg

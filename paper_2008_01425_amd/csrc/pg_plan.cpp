@@ -71,6 +71,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         L.p = p;
         L.q = q;
         L.r = std::min(rank, std::min(p, q));
+        P.max_layer_rank = std::max(P.max_layer_rank, L.r);
         L.V = (q % 4 == 0) ? 4 : (q % 2 == 0 ? 2 : 1);
         L.x_off = off;
         off = round_up(off + (int64_t)p * q, 4);
@@ -174,7 +175,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         g.lg = best;
         int row_groups = 4 * (64 / g.lg);
         int64_t row_bytes = (int64_t)g.lg * L.V * 4;
-        int64_t want = std::max<int64_t>(1, (col_heavy ? std::min(tn.col_tile_bytes, 128 * 1024) : tn.col_tile_bytes) / row_bytes);
+        int64_t want = std::max<int64_t>(1, tn.col_tile_bytes / row_bytes);
         int64_t unit = (int64_t)row_groups * kColUnroll;
         int64_t br = round_up(want, unit);
         if (br >= L.p) br = L.p;
@@ -274,6 +275,21 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     o = (size_t)round_up(o + (size_t)pho * 4, 256);
     P.ws_flag = o;
     o = (size_t)round_up(o + (size_t)flo * 4, 256);
+    // tall layers: row chunks for the two-kernel orthonormalisation (36 Gram sums per chunk)
+    P.orth_tiles.clear();
+    bool tall = false;
+    for (int l = 0; l < n_layers; ++l) tall = tall || P.layers[l].p > kOrthChunkRows;
+    if (tall) {
+        for (size_t el = 0; el < P.els.size(); ++el) {
+            const int p = P.els[el].p;
+            const int nch = (p + kOrthChunkRows - 1) / kOrthChunkRows;
+            for (int ch = 0; ch < nch; ++ch)
+                P.orth_tiles.push_back({(int32_t)el, ch * kOrthChunkRows,
+                                        std::min(kOrthChunkRows, p - ch * kOrthChunkRows), ch, nch, 0});
+        }
+    }
+    P.ws_gpart = o;
+    o = (size_t)round_up(o + P.orth_tiles.size() * 36 * 8, 256);
     P.ws_bytes = std::max<size_t>(o, 256);
 
     // ---- tiles, grouped by kernel instantiation, in address order ----

@@ -50,7 +50,7 @@ struct Plan {
     std::vector<int64_t> q_off;              // [e * L + l]
 
     // workspace sections (byte offsets) and their sizes
-    size_t ws_pw = 0, ws_qw = 0, ws_pd = 0, ws_ph = 0, ws_flag = 0, ws_bytes = 0;
+    size_t ws_pw = 0, ws_qw = 0, ws_pd = 0, ws_ph = 0, ws_flag = 0, ws_gpart = 0, ws_bytes = 0;
     std::vector<int64_t> ph_off;             // [e * L + l] float offset inside the Phat section
     std::vector<int64_t> flag_off;           // [e * L + l] int32 index inside the flag section
 
@@ -58,9 +58,10 @@ struct Plan {
     std::vector<ColDesc> cols;
     std::vector<EdgeLayerDesc> els;          // [l * n_edges + e]
     std::vector<CombTile> comb_tiles;
+    std::vector<OrthTile> orth_tiles;        // filled only when some layer has more than one row chunk
     std::vector<RowClass> row_classes;
     std::vector<ColClass> col_classes;
-    int orth_threads = 256;
+    int max_layer_rank = 1;                  // largest r_l
 };
 
 // Rows one work-group covers per pass for a compiled column count (register blocking).

@@ -141,7 +141,7 @@ struct Launcher {
                 tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, qstate, ph(), pw());
         } else {
             // register budget: RC accumulators and RC update coefficients per row
-            constexpr int M = 4;
+            constexpr int M = (UPD && SWP) ? 2 : 4;
             size_t lds = (size_t)RC * rc.max_seg * sizeof(float);
             row_wide_kernel<RC, M, UPD, SWP><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>(
                 tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, qstate, ph(), pw());
@@ -150,7 +150,7 @@ struct Launcher {
     template <int RC>
     void row_mode(const RowClass &rc, bool upd, bool swp) {
         if (upd && swp) {
-            if constexpr (RC < kWideCols) {
+            if constexpr (RC <= kWideCols) {
                 row_launch<RC, true, true>(rc);
             } else {
                 // with many stacked columns the fused pass does not fit in registers and is bound
@@ -231,10 +231,12 @@ struct Launcher {
         if (status || c->plan.els.empty()) return;
         begin(K_ORTH_P, 0.0);
         const int rmax = c->plan.max_layer_rank;
-        if (rmax <= 1) orth_launch<kOrthThreads, 1>();
-        else if (rmax <= 2) orth_launch<kOrthThreads, 2>();
-        else if (rmax <= 4) orth_launch<kOrthThreads, 4>();
-        else if (rmax <= 8) orth_launch<512, 8>();
+        // short layers: small work-groups, so that many (edge, layer) pairs share a CU
+        const bool small = c->plan.max_rows <= 2048;
+        if (rmax <= 1) small ? orth_launch<256, 1>() : orth_launch<kOrthThreads, 1>();
+        else if (rmax <= 2) small ? orth_launch<256, 2>() : orth_launch<kOrthThreads, 2>();
+        else if (rmax <= 4) small ? orth_launch<256, 4>() : orth_launch<kOrthThreads, 4>();
+        else if (rmax <= 8) small ? orth_launch<256, 8>() : orth_launch<512, 8>();
         else orth_kernel<kOrthThreads><<<dim3((unsigned)c->plan.els.size()), dim3(kOrthThreads), 0, st>>>(
             c->d_els, pw(), pdb(), ph(), flags());
         check();

@@ -72,6 +72,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         L.q = q;
         L.r = std::min(rank, std::min(p, q));
         P.max_layer_rank = std::max(P.max_layer_rank, L.r);
+        P.max_rows = std::max(P.max_rows, p);
         L.V = (q % 4 == 0) ? 4 : (q % 2 == 0 ? 2 : 1);
         L.x_off = off;
         off = round_up(off + (int64_t)p * q, 4);

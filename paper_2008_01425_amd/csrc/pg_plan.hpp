@@ -62,6 +62,7 @@ struct Plan {
     std::vector<RowClass> row_classes;
     std::vector<ColClass> col_classes;
     int max_layer_rank = 1;                  // largest r_l
+    int max_rows = 1;                        // largest p_l
 };
 
 // Rows one work-group covers per pass for a compiled column count (register blocking).

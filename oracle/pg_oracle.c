@@ -102,10 +102,14 @@ static void mat_t_vec(const real_t *X, int p, int q, const real_t *u, double *y)
  *   Phat       NULL, or [n_edges] pointers (entries may be NULL) receiving the last
  *              step's r_l orthonormal columns of length p (column k at +k*p)
  *   degenerate NULL, or [n_edges * r_l] flags of the last step
+ *   G, eta     NULL, or [n_workers] pointers to p*q stochastic gradients and the learning rate:
+ *              line 6 of Algorithm 1, X_i <- X_i + sum_j W_ij C(X_j - X_i) - eta * G_i, the
+ *              gradient term added to the same single rounding as the gossip term
  */
-int pgo_round_layer(int n_workers, int n_edges, const int32_t *edges, const double *edge_w,
-                    int p, int q, int rank, int power_steps,
-                    real_t *const *X, real_t *const *Q, real_t *const *Phat, int32_t *degenerate)
+int pgo_round_layer_sgd(int n_workers, int n_edges, const int32_t *edges, const double *edge_w,
+                        int p, int q, int rank, int power_steps,
+                        real_t *const *X, real_t *const *Q, real_t *const *Phat, int32_t *degenerate,
+                        const real_t *const *G, double eta)
 {
     if (n_workers < 1 || n_edges < 0 || p < 1 || q < 1 || rank < 1 || power_steps < 1)
         return PGO_ERR_ARG;
@@ -209,6 +213,10 @@ int pgo_round_layer(int n_workers, int n_edges, const int32_t *edges, const doub
                 }
             }
         }
+        if (G && G[i]) {
+            for (size_t t = 0; t < pq; ++t) dX[t] -= eta * (double)G[i][t];
+            touched = 1;
+        }
         if (touched)
             for (size_t t = 0; t < pq; ++t)
                 X[i][t] = (real_t)((double)X[i][t] + dX[t]);
@@ -225,4 +233,13 @@ int pgo_round_layer(int n_workers, int n_edges, const int32_t *edges, const doub
 
     free(pa); free(pb); free(qa); free(qb); free(P); free(Ph); free(Qc); free(deg); free(dX);
     return PGO_OK;
+}
+
+/* The gossip-only round (compressed consensus, Eq. (4)). */
+int pgo_round_layer(int n_workers, int n_edges, const int32_t *edges, const double *edge_w,
+                    int p, int q, int rank, int power_steps,
+                    real_t *const *X, real_t *const *Q, real_t *const *Phat, int32_t *degenerate)
+{
+    return pgo_round_layer_sgd(n_workers, n_edges, edges, edge_w, p, q, rank, power_steps,
+                               X, Q, Phat, degenerate, NULL, 0.0);
 }

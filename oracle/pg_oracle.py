@@ -52,6 +52,8 @@ def _lib(kind: str):
             ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.pgo_round_layer_sgd.restype = ctypes.c_int
+        lib.pgo_round_layer_sgd.argtypes = lib.pgo_round_layer.argtypes + [ctypes.c_void_p, ctypes.c_double]
         assert lib.pgo_real_bytes() == (4 if kind == "f32" else 8)
         _loaded[kind] = lib
     return _loaded[kind]
@@ -96,8 +98,9 @@ def _ptr_array(arrs: Sequence[Optional[np.ndarray]]):
 
 
 def round_layer(prob: Problem, l: int, X_l: Sequence[np.ndarray], Q_l: Sequence[np.ndarray],
-                want_phat: bool = True):
+                want_phat: bool = True, G_l: Optional[Sequence[np.ndarray]] = None, eta: float = 0.0):
     """One round on layer ``l``: X_l[i] (p, q) and Q_l[e] (r_l, q) are updated in place.
+    With G_l (one gradient per worker) the step is Algorithm 1's: gossip term minus eta * G.
 
     Returns (phat, degenerate): phat[e] is (r_l, p) or None; degenerate is (E, r_l) int32.
     """
@@ -112,27 +115,36 @@ def round_layer(prob: Problem, l: int, X_l: Sequence[np.ndarray], Q_l: Sequence[
     assert len(X_l) == prob.n_workers and len(Q_l) == prob.n_edges
     phat = [np.zeros((r, p), dtype=dt) for _ in range(prob.n_edges)] if want_phat else None
     deg = np.zeros((prob.n_edges, r), dtype=np.int32)
-    rc = _lib(kind).pgo_round_layer(
+    if G_l is not None:
+        for a in G_l:
+            assert a.dtype == dt and a.shape == (p, q) and a.flags.c_contiguous
+        assert len(G_l) == prob.n_workers
+    rc = _lib(kind).pgo_round_layer_sgd(
         prob.n_workers, prob.n_edges, prob.edges.ctypes.data, prob.edge_w.ctypes.data,
         p, q, prob.rank, prob.power_steps,
         ctypes.cast(_ptr_array(X_l), ctypes.c_void_p),
         ctypes.cast(_ptr_array(Q_l), ctypes.c_void_p),
         ctypes.cast(_ptr_array(phat), ctypes.c_void_p) if want_phat else None,
-        deg.ctypes.data)
+        deg.ctypes.data,
+        ctypes.cast(_ptr_array(G_l), ctypes.c_void_p) if G_l is not None else None,
+        float(eta))
     if rc != 0:
         raise ValueError(f"pgo_round_layer failed with code {rc}")
     return phat, deg
 
 
 def gossip_round(prob: Problem, X, Q, layers: Optional[Sequence[int]] = None,
-                 want_phat: bool = False) -> RoundInfo:
-    """One PowerGossip round over the chosen layers (default: all), in place."""
+                 want_phat: bool = False, G=None, eta: float = 0.0) -> RoundInfo:
+    """One PowerGossip round over the chosen layers (default: all), in place.  With G[i][l]
+    (gradients laid out like X) it is one step of Algorithm 1 with learning rate eta."""
     info = RoundInfo()
     ls = range(len(prob.shapes)) if layers is None else layers
     per_layer_phat = []
     for l in ls:
         ph, deg = round_layer(prob, l, [X[i][l] for i in range(prob.n_workers)],
-                              [Q[e][l] for e in range(prob.n_edges)], want_phat=want_phat)
+                              [Q[e][l] for e in range(prob.n_edges)], want_phat=want_phat,
+                              G_l=None if G is None else [G[i][l] for i in range(prob.n_workers)],
+                              eta=eta)
         per_layer_phat.append(ph)
         info.degenerate.append(deg)
     if want_phat:

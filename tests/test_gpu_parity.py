@@ -95,6 +95,40 @@ def test_many_tiles_and_tail_rows():
     _check(wl, 2, TOL_10, fused=True)
 
 
+def test_tall_embedding_shaped_layer():
+    """33278 x 650: rows only 8-byte aligned, row chunks in the orthonormalisation, many row blocks."""
+    wl = _custom("tall_embedding", 3, W.ring_edges(3), 1 / 3, [(33278, 650)], 2, 2, sigma=0.01)
+    _check(wl, 1, TOL_1)
+    _check(wl, 2, TOL_10, fused=True)
+
+
+def test_random_projections_fresh_state_every_round():
+    """Section 5, 'Random projections vs. power iteration': the same round with a fresh N(0,1)
+    projection every time instead of the warm start -- the caller simply refills the state.
+    The paper's consensus setting: 8-ring, W_ij = 0.436, 100 x 100 standard normal matrices."""
+    from paper_2008_01425_amd.device import GossipBuffers
+    from parity_util import oracle_problem
+    from oracle import pg_oracle as O
+    n = 8
+    wl = W.Workload("consensus_gauss", n, W.ring_edges(n), np.full((n,), 0.436, np.float32),
+                    [(100, 100)], 1, 1, 1.0, 10, 7)
+    rng = np.random.default_rng(123)
+    X = [[rng.standard_normal((100, 100)).astype(np.float32)] for _ in range(n)]
+    gb = GossipBuffers.from_workload(wl, fill=False)
+    for i in range(n):
+        gb.set_layer(i, 0, X[i][0])
+    prob = oracle_problem(wl)
+    for t in range(5):
+        Q = [[rng.standard_normal((1, 100)).astype(np.float32)] for _ in range(n)]
+        for e in range(n):
+            gb.set_q(e, 0, Q[e][0])
+        gb.round()
+        O.gossip_round(prob, X, Q)
+    for i in range(n):
+        assert rel_err(gb.get_layer(i, 0), X[i][0]) <= TOL_10
+    gb.close()
+
+
 # ------------------------------------------------------------------ degenerate cases
 def test_identical_workers_are_a_fixed_point():
     from paper_2008_01425_amd.device import GossipBuffers

@@ -404,3 +404,83 @@ def test_vector_lengths_reproduce_the_printed_compression_ratios():
         else:
             sent_odd, sent_even = p, q
         assert round(p * q / ((sent_odd + sent_even) / 2)) == printed
+
+
+# ------------------------------------------- Theorem 1 with random projections
+def test_random_left_projections_contract_at_the_rate_of_theorem_1():
+    """Theorem 1: with delta-approximate projections the expected squared distance to the mean
+    shrinks by (1 - rho * delta) per round, rho = 1 - lambda_2(W)^2.  One power step from a fresh
+    N(0,1) vector applies a rank-1 left projection Phat Phat^T with Phat = DQ/|DQ|; for an iid
+    Gaussian difference that direction is (nearly) uniform on the sphere, delta = 1/p (Section
+    4.1).  Averaged over many rounds the measured contraction must not be slower than the bound
+    (it is an upper bound) and, on unstructured data, not much faster either."""
+    rng = np.random.default_rng(21)
+    n, p, q, w = 8, 12, 12, 0.436
+    edges = ring(n)
+    Wm = np.zeros((n, n))
+    for a, b in edges:
+        Wm[a, b] = Wm[b, a] = w
+    Wm += np.diag(1 - Wm.sum(1))
+    lam = np.sort(np.abs(np.linalg.eigvalsh(Wm)))[::-1]
+    rho = 1 - lam[1] ** 2
+    delta = 1.0 / p
+    prob = make(n, edges, w, [(p, q)])
+    ratios = []
+    for trial in range(40):
+        X = [[rng.standard_normal((p, q))] for _ in range(n)]
+        d0 = consensus_distance(X)
+        Q = [[rng.standard_normal((1, q))] for _ in range(n)]
+        O.gossip_round(prob, X, Q)
+        ratios.append(consensus_distance(X) / d0)
+    mean = float(np.mean(ratios))
+    assert mean <= 1 - rho * delta + 0.01
+    assert mean >= 1 - 6 * rho * delta        # sanity: a rank-1 step cannot contract like full gossip
+
+
+# ------------------------------------------------ Algorithm 1, line 6: the gradient term
+def test_sgd_term_without_edges_is_plain_sgd():
+    """Algorithm 1, line 6 with no neighbours: X <- X - eta * G."""
+    rng = np.random.default_rng(30)
+    prob = make(3, np.zeros((0, 2), np.int32), np.zeros(0), [(5, 4), (3, 1)])
+    X, Q = rand_state(prob, rng)
+    G = [[rng.standard_normal(a.shape) for a in row] for row in X]
+    X0 = [[a.copy() for a in row] for row in X]
+    O.gossip_round(prob, X, Q, G=G, eta=0.1)
+    for i in range(3):
+        for l in range(2):
+            assert np.allclose(X[i][l], X0[i][l] - 0.1 * G[i][l], atol=1e-15)
+
+
+def test_sgd_term_adds_to_the_gossip_term_and_moves_the_mean_by_the_mean_gradient():
+    """Algorithm 1, line 6 is one expression: gossip correction (from the start-of-round
+    parameters) minus eta * G.  So the result is the gossip-only result minus eta * G, the
+    projection state is unaffected by G, and the worker mean moves by -eta * mean(G) (Lemma 1
+    plus the gradient term)."""
+    rng = np.random.default_rng(31)
+    n = 5
+    prob = make(n, ring(n), 1 / 3, [(7, 6), (4, 1)], rank=2, steps=2)
+    X, Q = rand_state(prob, rng)
+    G = [[rng.standard_normal(a.shape) for a in row] for row in X]
+    Xp, Qp = copy_state(X, Q)
+    mean0 = [sum(X[i][l] for i in range(n)) / n for l in range(2)]
+    O.gossip_round(prob, X, Q, G=G, eta=0.05)
+    O.gossip_round(prob, Xp, Qp)
+    for l in range(2):
+        for i in range(n):
+            assert np.allclose(X[i][l], Xp[i][l] - 0.05 * G[i][l], atol=1e-14)
+        gm = sum(G[i][l] for i in range(n)) / n
+        assert np.allclose(sum(X[i][l] for i in range(n)) / n, mean0[l] - 0.05 * gm, atol=1e-14)
+        for e in range(n):
+            assert np.array_equal(Q[e][l], Qp[e][l])
+
+
+def test_zero_gradient_is_the_gossip_round_bitwise():
+    rng = np.random.default_rng(32)
+    prob = make(4, ring(4), 1 / 3, [(6, 5)], rank=1)
+    X, Q = rand_state(prob, rng, np.float32)
+    Xp, Qp = copy_state(X, Q)
+    G = [[np.zeros_like(a) for a in row] for row in X]
+    O.gossip_round(prob, X, Q, G=G, eta=0.3)
+    O.gossip_round(prob, Xp, Qp)
+    for i in range(4):
+        assert np.array_equal(X[i][0], Xp[i][0])

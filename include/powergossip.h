@@ -153,6 +153,21 @@ int pg_round(pg_ctx *ctx, float *const *worker_params, float *q_state, void *wor
              void *hip_stream);
 
 /*
+ * One step of decentralized SGD with edge-wise compression (Algorithm 1, line 6):
+ *     X_i <- X_i + sum_j W_ij C(X_j - X_i) - eta * G_i
+ * i.e. pg_round with the stochastic-gradient term folded into the update pass (the update then
+ * reads X and G and writes X once: 12 instead of 8 + 12 bytes per parameter for a separate
+ * SGD step).  Both terms enter one double-precision sum that is rounded to float once.
+ *   worker_grads   host array of n_workers DEVICE pointers, laid out like the parameter
+ *                  buffers (pg_param_floats floats, same layer offsets), 16-byte aligned;
+ *                  read only.  Cached like worker_params.
+ *   eta            learning rate (finite)
+ * Workers without edges get X_i -= eta * G_i.  Other arguments and errors as pg_round.
+ */
+int pg_round_sgd(pg_ctx *ctx, float *const *worker_params, const float *const *worker_grads,
+                 float eta, float *q_state, void *workspace, void *hip_stream);
+
+/*
  * `rounds` consecutive gossip rounds with nothing touching the parameters in between
  * (the pure consensus iteration, Eq. (4)).  Same result as calling pg_round `rounds` times;
  * the update of round t and the first product of round t+1 share one pass over the
@@ -167,7 +182,7 @@ int pg_run(pg_ctx *ctx, float *const *worker_params, float *q_state, void *works
  * adds them up per kernel kind since the previous collect, and clears the record.
  */
 typedef struct pg_kernel_time {
-    char name[32];   /* "sweep_p", "orth_p", "sweep_q", "combine_q", "update", "update_sweep_p" */
+    char name[32];   /* "sweep_p", "orth_p", "sweep_q", "combine_q", "update", "update_sweep_p", "update_sgd" */
     int launches;    /* kernel launches of this kind */
     double ms;       /* summed duration */
     double bytes;    /* summed algorithmic bytes of parameter traffic (4 B per element read or written) */

@@ -17,7 +17,8 @@ PG_OK, PG_ERR_ARG, PG_ERR_TOPOLOGY, PG_ERR_SHAPE, PG_ERR_NOMEM, PG_ERR_DEVICE = 
 EXPORTS = [
     "pg_strerror", "pg_init", "pg_destroy", "pg_param_floats", "pg_layer_offset", "pg_layer_rank",
     "pg_qstate_floats", "pg_q_offset", "pg_workspace_bytes", "pg_ws_phat_offset",
-    "pg_ws_flag_offset", "pg_message_floats", "pg_round_bytes", "pg_upload", "pg_round", "pg_run",
+    "pg_ws_flag_offset", "pg_message_floats", "pg_round_bytes", "pg_upload", "pg_round", "pg_round_sgd",
+    "pg_run",
     "pg_profile_enable", "pg_profile_collect",
 ]
 
@@ -53,6 +54,8 @@ def _load():
     lib.pg_upload.argtypes = [vp]
     lib.pg_round.restype = ci
     lib.pg_round.argtypes = [vp, vp, vp, vp, vp]
+    lib.pg_round_sgd.restype = ci
+    lib.pg_round_sgd.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp]
     lib.pg_run.restype = ci
     lib.pg_run.argtypes = [vp, vp, vp, vp, vp, ci]
     lib.pg_profile_enable.restype = ci
@@ -123,6 +126,12 @@ def _ptr_table(worker_ptrs: Sequence[int]):
 def pg_round(ctx, worker_ptrs: Sequence[int], q_ptr: int, ws_ptr: int, stream: int = 0) -> None:
     """worker_ptrs: device addresses of the n parameter buffers; q_ptr / ws_ptr: device addresses."""
     _check(lib.pg_round(ctx, _ptr_table(worker_ptrs), q_ptr, ws_ptr, stream))
+
+
+def pg_round_sgd(ctx, worker_ptrs: Sequence[int], grad_ptrs: Sequence[int], eta: float, q_ptr: int,
+                 ws_ptr: int, stream: int = 0) -> None:
+    """grad_ptrs: device addresses of the n gradient buffers (laid out like the parameters)."""
+    _check(lib.pg_round_sgd(ctx, _ptr_table(worker_ptrs), _ptr_table(grad_ptrs), eta, q_ptr, ws_ptr, stream))
 
 
 def pg_run(ctx, worker_ptrs: Sequence[int], q_ptr: int, ws_ptr: int, stream: int, rounds: int) -> None:

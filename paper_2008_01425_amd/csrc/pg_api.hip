@@ -17,9 +17,9 @@ namespace {
 
 constexpr int kOrthThreads = 1024;
 
-enum Kind { K_SWEEP_P = 0, K_ORTH_P, K_SWEEP_Q, K_COMBINE_Q, K_UPDATE, K_UPDATE_SWEEP_P, K_COUNT };
-const char *const kKindName[K_COUNT] = {"sweep_p", "orth_p",  "sweep_q",
-                                        "combine_q", "update", "update_sweep_p"};
+enum Kind { K_SWEEP_P = 0, K_ORTH_P, K_SWEEP_Q, K_COMBINE_Q, K_UPDATE, K_UPDATE_SWEEP_P, K_UPDATE_SGD, K_COUNT };
+const char *const kKindName[K_COUNT] = {"sweep_p", "orth_p",  "sweep_q", "combine_q",
+                                        "update",  "update_sweep_p", "update_sgd"};
 
 struct ProfRec {
     int kind;
@@ -39,8 +39,11 @@ struct pg_ctx {
     EdgeLayerDesc *d_els = nullptr;
     CombTile *d_comb = nullptr;
     OrthTile *d_orth = nullptr;
+    int32_t *d_iso = nullptr;
     float **d_xs = nullptr;
     std::vector<float *> xs_cached;
+    float **d_gs = nullptr;
+    std::vector<const float *> gs_cached;
     bool profiling = false;
     int col_reverse = 1;
     std::vector<ProfRec> recs;
@@ -87,7 +90,9 @@ int do_upload(pg_ctx *c) {
     if ((rc = upload_vec(&c->d_els, P.els))) return rc;
     if ((rc = upload_vec(&c->d_comb, P.comb_tiles))) return rc;
     if ((rc = upload_vec(&c->d_orth, P.orth_tiles))) return rc;
+    if ((rc = upload_vec(&c->d_iso, P.isolated_pairs))) return rc;
     PG_HIP(hipMalloc((void **)&c->d_xs, sizeof(float *) * (size_t)P.n));
+    PG_HIP(hipMalloc((void **)&c->d_gs, sizeof(float *) * (size_t)P.n));
     c->uploaded = true;
     return PG_OK;
 }
@@ -97,6 +102,7 @@ struct Launcher {
     hipStream_t st;
     float *qstate;
     char *ws;
+    double eta = 0.0;  // learning rate of the fused gradient term (pg_round_sgd only)
     int status = PG_OK;
 
     double *pw() const { return (double *)(ws + c->plan.ws_pw); }
@@ -131,25 +137,28 @@ struct Launcher {
         if (hipGetLastError() != hipSuccess) status = PG_ERR_DEVICE;
     }
 
-    template <int RC, bool UPD, bool SWP>
+    template <int RC, bool UPD, bool SWP, bool GRAD = false>
     void row_launch(const RowClass &rc) {
         const int n = (int)rc.tiles.size();
         const RowTile *tiles = c->d_row_tiles + rc.dev_first;
         if constexpr (RC < kWideCols) {
-            constexpr int M = (RC <= 2) ? 8 : 4;
-            row_kernel<RC, M, UPD, SWP><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
-                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, qstate, ph(), pw());
+            // the gradient slice is prefetched like X: halve the row blocking to stay in registers
+            constexpr int M = (RC <= 2) ? (GRAD ? 4 : 8) : 4;
+            row_kernel<RC, M, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
+                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, qstate, ph(), pw(), c->d_gs, eta);
         } else {
             // register budget: RC accumulators and RC update coefficients per row
-            constexpr int M = (UPD && SWP) ? 2 : 4;
+            constexpr int M = ((UPD && SWP) || GRAD) ? 2 : 4;
             size_t lds = (size_t)RC * rc.max_seg * sizeof(float);
-            row_wide_kernel<RC, M, UPD, SWP><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>(
-                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, qstate, ph(), pw());
+            row_wide_kernel<RC, M, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>(
+                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, qstate, ph(), pw(), c->d_gs, eta);
         }
     }
     template <int RC>
-    void row_mode(const RowClass &rc, bool upd, bool swp) {
-        if (upd && swp) {
+    void row_mode(const RowClass &rc, bool upd, bool swp, bool grad) {
+        if (grad) {
+            row_launch<RC, true, false, true>(rc);
+        } else if (upd && swp) {
             if constexpr (RC <= kWideCols) {
                 row_launch<RC, true, true>(rc);
             } else {
@@ -164,23 +173,34 @@ struct Launcher {
             row_launch<RC, false, true>(rc);
         }
     }
-    // One pass of the row-owner kernels over every parameter, front to back: sweep, update, or both.
-    void rows(bool upd, bool swp) {
+    // One pass of the row-owner kernels over every parameter, front to back: sweep, update, or
+    // both; `grad` = update with the gradient term (X -= eta * G) in the same pass.
+    void rows(bool upd, bool swp, bool grad = false) {
         if (status) return;
-        int kind = upd ? (swp ? K_UPDATE_SWEEP_P : K_UPDATE) : K_SWEEP_P;
+        int kind = grad ? K_UPDATE_SGD : (upd ? (swp ? K_UPDATE_SWEEP_P : K_UPDATE) : K_SWEEP_P);
         for (const RowClass &rc : c->plan.row_classes) {
             if (rc.tiles.empty()) continue;
-            begin(kind, rc.elems * 4.0 * (upd ? 2.0 : 1.0));
+            begin(kind, rc.elems * 4.0 * (grad ? 3.0 : (upd ? 2.0 : 1.0)));
             switch (rc.RC) {
-                case 1: row_mode<1>(rc, upd, swp); break;
-                case 2: row_mode<2>(rc, upd, swp); break;
-                case 4: row_mode<4>(rc, upd, swp); break;
-                case 8: row_mode<8>(rc, upd, swp); break;
-                default: row_mode<16>(rc, upd, swp); break;
+                case 1: row_mode<1>(rc, upd, swp, grad); break;
+                case 2: row_mode<2>(rc, upd, swp, grad); break;
+                case 4: row_mode<4>(rc, upd, swp, grad); break;
+                case 8: row_mode<8>(rc, upd, swp, grad); break;
+                default: row_mode<16>(rc, upd, swp, grad); break;
             }
             check();
             end();
         }
+    }
+    // Workers without edges: their whole step is X -= eta * G.
+    void sgd_isolated() {
+        const Plan &P = c->plan;
+        if (status || P.isolated_pairs.empty()) return;
+        begin(K_UPDATE_SGD, P.isolated_elems * 12.0);
+        sgd_only_kernel<<<dim3(64, (unsigned)P.isolated_pairs.size()), dim3(kThreads), 0, st>>>(
+            c->d_iso, c->d_pairs, c->d_xs, c->d_gs, eta);
+        check();
+        end();
     }
 
     // The Q-sweep walks the parameters back to front: it starts on what the pass before it
@@ -272,6 +292,21 @@ int prepare(pg_ctx *c, float *const *worker_params, float *q_state, void *worksp
     return PG_OK;
 }
 
+int prepare_grads(pg_ctx *c, const float *const *worker_grads, hipStream_t st) {
+    const Plan &P = c->plan;
+    if (!worker_grads) return PG_ERR_ARG;
+    for (int i = 0; i < P.n; ++i)
+        if (!worker_grads[i] || ((uintptr_t)worker_grads[i] & 15)) return PG_ERR_ARG;
+    bool same = c->gs_cached.size() == (size_t)P.n;
+    for (int i = 0; same && i < P.n; ++i) same = c->gs_cached[i] == worker_grads[i];
+    if (!same) {
+        PG_HIP(hipStreamSynchronize(st));
+        c->gs_cached.assign(worker_grads, worker_grads + P.n);
+        PG_HIP(hipMemcpy(c->d_gs, c->gs_cached.data(), sizeof(float *) * (size_t)P.n, hipMemcpyHostToDevice));
+    }
+    return PG_OK;
+}
+
 int run_rounds(pg_ctx *c, float *const *worker_params, float *q_state, void *workspace,
                void *hip_stream, int rounds, bool fuse) {
     hipStream_t st = (hipStream_t)hip_stream;
@@ -350,6 +385,8 @@ int pg_destroy(pg_ctx *c) {
         (void)hipFree(c->d_comb);
         (void)hipFree(c->d_orth);
         (void)hipFree(c->d_xs);
+        (void)hipFree(c->d_gs);
+        (void)hipFree(c->d_iso);
     }
     delete c;
     return PG_OK;
@@ -392,6 +429,29 @@ int pg_upload(pg_ctx *c) {
 
 int pg_round(pg_ctx *c, float *const *worker_params, float *q_state, void *workspace, void *hip_stream) {
     return run_rounds(c, worker_params, q_state, workspace, hip_stream, 1, false);
+}
+
+int pg_round_sgd(pg_ctx *c, float *const *worker_params, const float *const *worker_grads, float eta,
+                 float *q_state, void *workspace, void *hip_stream) {
+    hipStream_t st = (hipStream_t)hip_stream;
+    int rc = prepare(c, worker_params, q_state, workspace, st);
+    if (rc) return rc;
+    if (!(eta == eta)) return PG_ERR_ARG;
+    if ((rc = prepare_grads(c, worker_grads, st))) return rc;
+    Launcher L{c, st, q_state, (char *)workspace};
+    L.eta = (double)eta;
+    const int s = c->plan.steps;
+    if (c->plan.n_edges > 0) {
+        for (int step = 0; step < s; ++step) {
+            L.rows(false, true);
+            L.orth_p();
+            L.sweep_q();
+            L.combine_q();
+        }
+        L.rows(true, false, /*grad=*/true);
+    }
+    L.sgd_isolated();
+    return L.status;
 }
 
 int pg_run(pg_ctx *c, float *const *worker_params, float *q_state, void *workspace,

@@ -105,11 +105,12 @@ __device__ __forceinline__ void group_sum_all(double (&v)[N], int width) {
 //   both  : the update, then the next round's sweep on the updated values -- the next
 //           round's right-hand side is exactly the Q' just applied (warm start).
 // ---------------------------------------------------------------------------------------
-template <int V, int RC, int M, bool UPDATE, bool SWEEP>
+template <int V, int RC, int M, bool UPDATE, bool SWEEP, bool GRAD>
 __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
                                          const ColDesc *__restrict__ cols, float *X,
                                          const float *__restrict__ qstate,
-                                         const float *__restrict__ phat, double *__restrict__ pw) {
+                                         const float *__restrict__ phat, double *__restrict__ pw,
+                                         const float *Gp, double eta) {
     typedef typename VecT<V>::T vec;
     const int lane = threadIdx.x;
     const int lpr = pd.lpr;
@@ -136,6 +137,7 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
 
     for (int rbase = t.row0 + grp * M; rbase < row_end; rbase += ngrp * M) {
         float *xrow[M];
+        const float *grow[M];
         bool ok[M];
         int rowi[M];
 #pragma unroll
@@ -143,6 +145,7 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
             ok[m] = rbase + m < row_end;
             rowi[m] = ok[m] ? rbase + m : row_end - 1;
             xrow[m] = X + (int64_t)rowi[m] * q;
+            grow[m] = GRAD ? Gp + (int64_t)rowi[m] * q : nullptr;
         }
         double cp[M][RC];
         if (UPDATE) {
@@ -158,13 +161,17 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
 #pragma unroll
             for (int j = 0; j < RC; ++j) acc[m][j] = 0.0;
 
-        auto load = [&](int c, vec(&xv)[M], vec(&qv)[RC]) {
+        auto load = [&](int c, vec(&xv)[M], vec(&qv)[RC], vec(&gv)[GRAD ? M : 1]) {
 #pragma unroll
             for (int j = 0; j < RC; ++j) qv[j] = ldg<V>(qcol[j] + c);
 #pragma unroll
             for (int m = 0; m < M; ++m) xv[m] = ldg<V>(xrow[m] + c);
+            if (GRAD) {
+#pragma unroll
+                for (int m = 0; m < M; ++m) gv[GRAD ? m : 0] = ldg<V>(grow[m] + c);
+            }
         };
-        auto process = [&](int c, vec(&xv)[M], vec(&qv)[RC]) {
+        auto process = [&](int c, vec(&xv)[M], vec(&qv)[RC], vec(&gv)[GRAD ? M : 1]) {
             double qd[RC][V];
 #pragma unroll
             for (int j = 0; j < RC; ++j)
@@ -180,6 +187,7 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
                     for (int v = 0; v < V; ++v) {
 #pragma unroll
                         for (int j = 0; j < RC; ++j) xd[v] = fma(-cp[m][j], qd[j][v], xd[v]);
+                        if (GRAD) xd[v] = fma(-eta, (double)gv[GRAD ? m : 0][v], xd[v]);
                         xv[m][v] = (float)xd[v];
                         xd[v] = (double)xv[m][v];  // the sweep uses the stored (rounded) value
                     }
@@ -196,29 +204,29 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
 
         int c = c_begin + sub * V;
         if (c < c_end) {
-            vec xa[M], qa[RC], xb[M], qb[RC];
+            vec xa[M], qa[RC], xb[M], qb[RC], ga[GRAD ? M : 1], gb[GRAD ? M : 1];
             int rem = (c_end - c - 1) / step;  // steps after the first one
             // PG_FENCE keeps the compiler from sinking a prefetch below the arithmetic it overlaps
-            load(c, xa, qa);
+            load(c, xa, qa, ga);
             while (rem >= 2) {
-                load(c + step, xb, qb);
+                load(c + step, xb, qb, gb);
                 PG_FENCE();
-                process(c, xa, qa);
+                process(c, xa, qa, ga);
                 PG_FENCE();
-                load(c + 2 * step, xa, qa);
+                load(c + 2 * step, xa, qa, ga);
                 PG_FENCE();
-                process(c + step, xb, qb);
+                process(c + step, xb, qb, gb);
                 PG_FENCE();
                 c += 2 * step;
                 rem -= 2;
             }
             if (rem == 1) {
-                load(c + step, xb, qb);
+                load(c + step, xb, qb, gb);
                 PG_FENCE();
-                process(c, xa, qa);
-                process(c + step, xb, qb);
+                process(c, xa, qa, ga);
+                process(c + step, xb, qb, gb);
             } else {
-                process(c, xa, qa);
+                process(c, xa, qa, ga);
             }
         }
         if (SWEEP) {
@@ -238,18 +246,21 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
 
 // One wavefront per tile; `reverse` walks the tile list backwards so that a pass can start on
 // the data the previous pass touched last (still resident in the memory-side cache).
-template <int RC, int M, bool UPDATE, bool SWEEP>
+//   GRAD  : (with UPDATE) also subtract eta * G[row, c]: line 6 of Algorithm 1 in one pass.
+template <int RC, int M, bool UPDATE, bool SWEEP, bool GRAD>
 __global__ void __launch_bounds__(kRowThreads)
 row_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
            const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
            float *const *__restrict__ xs, const float *__restrict__ qstate,
-           const float *__restrict__ phat, double *__restrict__ pw) {
+           const float *__restrict__ phat, double *__restrict__ pw,
+           const float *const *__restrict__ gs, double eta) {
     const RowTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
     const PairDesc pd = pairs[t.pair];
     float *X = xs[pd.worker] + pd.x_off;
-    if (pd.V == 4) row_body<4, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw);
-    else if (pd.V == 2) row_body<2, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw);
-    else row_body<1, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw);
+    const float *Gp = GRAD ? gs[pd.worker] + pd.x_off : nullptr;
+    if (pd.V == 4) row_body<4, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
+    else if (pd.V == 2) row_body<2, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
+    else row_body<1, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -258,12 +269,13 @@ row_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
 // RC columns without the Q slice being re-fetched per row.  Lane groups own M rows each as in
 // the narrow kernel; only X is prefetched a step ahead, in registers.
 // ---------------------------------------------------------------------------------------
-template <int V, int RC, int M, bool UPDATE, bool SWEEP>
+template <int V, int RC, int M, bool UPDATE, bool SWEEP, bool GRAD>
 __device__ __forceinline__ void row_wide_body(const RowTile &t, const PairDesc &pd,
                                               const ColDesc *__restrict__ cols, float *X,
                                               const float *__restrict__ qstate,
                                               const float *__restrict__ phat,
-                                              double *__restrict__ pw, float *sQ) {
+                                              double *__restrict__ pw, float *sQ,
+                                              const float *Gp, double eta) {
     typedef typename VecT<V>::T vec;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lpr = pd.lpr;
@@ -308,6 +320,7 @@ __device__ __forceinline__ void row_wide_body(const RowTile &t, const PairDesc &
 
     for (int rbase = t.row0 + grp * M; rbase < row_end; rbase += ngrp * M) {
         float *xrow[M];
+        const float *grow[M];
         bool ok[M];
         int rowi[M];
 #pragma unroll
@@ -315,6 +328,7 @@ __device__ __forceinline__ void row_wide_body(const RowTile &t, const PairDesc &
             ok[m] = rbase + m < row_end;
             rowi[m] = ok[m] ? rbase + m : row_end - 1;
             xrow[m] = X + (int64_t)rowi[m] * q;
+            grow[m] = GRAD ? Gp + (int64_t)rowi[m] * q : nullptr;
         }
         double cp[M][RC];
         if (UPDATE) {
@@ -330,11 +344,15 @@ __device__ __forceinline__ void row_wide_body(const RowTile &t, const PairDesc &
 #pragma unroll
             for (int j = 0; j < RC; ++j) acc[m][j] = 0.0;
 
-        auto load = [&](int c, vec(&xv)[M]) {
+        auto load = [&](int c, vec(&xv)[M], vec(&gv)[GRAD ? M : 1]) {
 #pragma unroll
             for (int m = 0; m < M; ++m) xv[m] = ldg<V>(xrow[m] + c);
+            if (GRAD) {
+#pragma unroll
+                for (int m = 0; m < M; ++m) gv[GRAD ? m : 0] = ldg<V>(grow[m] + c);
+            }
         };
-        auto process = [&](int c, vec(&xv)[M]) {
+        auto process = [&](int c, vec(&xv)[M], vec(&gv)[GRAD ? M : 1]) {
             const float *sq = sQ + (c - c_begin);
             double xd[M][V];
 #pragma unroll
@@ -356,6 +374,7 @@ __device__ __forceinline__ void row_wide_body(const RowTile &t, const PairDesc &
                 for (int m = 0; m < M; ++m) {
 #pragma unroll
                     for (int v = 0; v < V; ++v) {
+                        if (GRAD) xd[m][v] = fma(-eta, (double)gv[GRAD ? m : 0][v], xd[m][v]);
                         xv[m][v] = (float)xd[m][v];
                         xd[m][v] = (double)xv[m][v];  // the sweep uses the stored (rounded) value
                     }
@@ -378,20 +397,24 @@ __device__ __forceinline__ void row_wide_body(const RowTile &t, const PairDesc &
 
         int c = c_begin + sub * V;
         if (c < c_end) {
-            vec xa[M], xb[M];
+            vec xa[M], xb[M], ga[GRAD ? M : 1], gb[GRAD ? M : 1];
             int rem = (c_end - c - 1) / step;  // steps after the first one
-            load(c, xa);
+            load(c, xa, ga);
 #pragma unroll 1
             for (; rem > 0; --rem) {
-                load(c + step, xb);
+                load(c + step, xb, gb);
                 PG_FENCE();
-                process(c, xa);
+                process(c, xa, ga);
                 PG_FENCE();
 #pragma unroll
                 for (int m = 0; m < M; ++m) xa[m] = xb[m];
+                if (GRAD) {
+#pragma unroll
+                    for (int m = 0; m < M; ++m) ga[GRAD ? m : 0] = gb[GRAD ? m : 0];
+                }
                 c += step;
             }
-            process(c, xa);
+            process(c, xa, ga);
         }
         if (SWEEP) {
             double(&flat)[M * RC] = reinterpret_cast<double(&)[M * RC]>(acc);
@@ -408,20 +431,36 @@ __device__ __forceinline__ void row_wide_body(const RowTile &t, const PairDesc &
     }
 }
 
-template <int RC, int M, bool UPDATE, bool SWEEP>
+template <int RC, int M, bool UPDATE, bool SWEEP, bool GRAD>
 __global__ void __launch_bounds__(kThreads)
 row_wide_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
                 const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
                 float *const *__restrict__ xs, const float *__restrict__ qstate,
-                const float *__restrict__ phat, double *__restrict__ pw) {
+                const float *__restrict__ phat, double *__restrict__ pw,
+                const float *const *__restrict__ gs, double eta) {
     extern __shared__ double smem[];
     float *sQ = reinterpret_cast<float *>(smem);
     const RowTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
     const PairDesc pd = pairs[t.pair];
     float *X = xs[pd.worker] + pd.x_off;
-    if (pd.V == 4) row_wide_body<4, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw, sQ);
-    else if (pd.V == 2) row_wide_body<2, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw, sQ);
-    else row_wide_body<1, RC, M, UPDATE, SWEEP>(t, pd, cols, X, qstate, phat, pw, sQ);
+    const float *Gp = GRAD ? gs[pd.worker] + pd.x_off : nullptr;
+    if (pd.V == 4) row_wide_body<4, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, sQ, Gp, eta);
+    else if (pd.V == 2) row_wide_body<2, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, sQ, Gp, eta);
+    else row_wide_body<1, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, sQ, Gp, eta);
+}
+
+// Workers without any edge receive no gossip term; with a gradient their step is plain SGD,
+// X -= eta * G, elementwise over the listed (worker, layer) pairs.
+__global__ void __launch_bounds__(kThreads)
+sgd_only_kernel(const int32_t *__restrict__ pair_ids, const PairDesc *__restrict__ pairs,
+                float *const *__restrict__ xs, const float *const *__restrict__ gs, double eta) {
+    const PairDesc pd = pairs[pair_ids[blockIdx.y]];
+    float *X = xs[pd.worker] + pd.x_off;
+    const float *G = gs[pd.worker] + pd.x_off;
+    const int64_t total = (int64_t)pd.p * pd.q;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * kThreads)
+        X[i] = (float)fma(-eta, (double)G[i], (double)X[i]);
 }
 
 // ---------------------------------------------------------------------------------------

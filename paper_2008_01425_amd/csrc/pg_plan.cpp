@@ -296,6 +296,8 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     // ---- tiles, grouped by kernel instantiation, in address order ----
     P.row_classes.clear();
     P.col_classes.clear();
+    P.isolated_pairs.clear();
+    P.isolated_elems = 0;
     auto row_class = [&](int RC) -> size_t {
         for (size_t k = 0; k < P.row_classes.size(); ++k)
             if (P.row_classes[k].RC == RC) return k;
@@ -314,7 +316,11 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         for (int i = 0; i < n_workers; ++i) {
             int pair = l * n_workers + i;
             const PairDesc &pd = P.pairs[pair];
-            if (pd.R == 0) continue;  // isolated worker: nothing to multiply or update
+            if (pd.R == 0) {  // isolated worker: nothing to multiply, no gossip term
+                P.isolated_pairs.push_back(pair);
+                P.isolated_elems += (double)L.p * L.q;
+                continue;
+            }
             int RC = compiled_cols(pd.R);
             RowClass &rc = P.row_classes[row_class(RC)];
             int rows_iter = g.rows_iter_base * rows_unroll(RC);

@@ -58,6 +58,8 @@ struct Plan {
     std::vector<ColDesc> cols;
     std::vector<EdgeLayerDesc> els;          // [l * n_edges + e]
     std::vector<CombTile> comb_tiles;
+    std::vector<int32_t> isolated_pairs;     // (worker, layer) pairs of workers without edges
+    double isolated_elems = 0;               // their parameter count
     std::vector<OrthTile> orth_tiles;        // filled only when some layer has more than one row chunk
     std::vector<RowClass> row_classes;
     std::vector<ColClass> col_classes;

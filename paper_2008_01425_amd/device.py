@@ -90,6 +90,20 @@ class GossipBuffers:
         s = torch.cuda.current_stream(self.device) if stream is None else stream
         B.pg_round(self.ctx, self.ptrs, self.q.data_ptr(), self.ws.data_ptr(), s.cuda_stream)
 
+    def alloc_grads(self):
+        """Gradient buffers laid out like the parameter buffers (zero-filled)."""
+        self.g = [torch.zeros(self.N, dtype=torch.float32, device=self.device) for _ in range(self.n)]
+        self.gptrs = [t.data_ptr() for t in self.g]
+
+    def set_grad_layer(self, i: int, l: int, a: np.ndarray):
+        p, q = self.shapes[l]
+        off = B.pg_layer_offset(self.ctx, l)
+        self.g[i][off:off + p * q].copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32).reshape(-1)))
+
+    def round_sgd(self, eta: float, stream: Optional[torch.cuda.Stream] = None):
+        s = torch.cuda.current_stream(self.device) if stream is None else stream
+        B.pg_round_sgd(self.ctx, self.ptrs, self.gptrs, eta, self.q.data_ptr(), self.ws.data_ptr(), s.cuda_stream)
+
     def run(self, rounds: int, stream: Optional[torch.cuda.Stream] = None):
         s = torch.cuda.current_stream(self.device) if stream is None else stream
         B.pg_run(self.ctx, self.ptrs, self.q.data_ptr(), self.ws.data_ptr(), s.cuda_stream, rounds)

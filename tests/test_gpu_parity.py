@@ -129,6 +129,83 @@ def test_random_projections_fresh_state_every_round():
     gb.close()
 
 
+# ------------------------------------------------------------------ Algorithm 1: fused gradient term
+def _check_sgd(wl, steps_eta, tol):
+    """pg_round_sgd against the oracle's Algorithm-1 step, fresh random gradients every step."""
+    from oracle import pg_oracle as O
+    from parity_util import oracle_problem
+    print(f"case sgd {wl.name}", flush=True)
+    gb = _gb(wl)
+    gb.alloc_grads()
+    layers = list(range(len(wl.shapes)))
+    X, Q = wl.all_params(), wl.all_q()
+    prob = oracle_problem(wl)
+    rng = np.random.default_rng(99)
+    for eta in steps_eta:
+        G = [[rng.standard_normal(s).astype(np.float32) for s in wl.shapes] for _ in range(wl.n_workers)]
+        for i in range(wl.n_workers):
+            for l in layers:
+                gb.set_grad_layer(i, l, G[i][l])
+        gb.round_sgd(eta)
+        O.gossip_round(prob, X, Q, G=G, eta=float(np.float32(eta)))
+    worst = compare_state(gb, X, Q, layers, tol, what="sgd " + wl.name)
+    print("   worst rel err", worst, flush=True)
+    gb.close()
+
+
+@pytest.mark.parametrize("rank,steps", [(1, 1), (2, 2), (4, 1)])
+def test_sgd_step_ragged_ring(rank, steps):
+    wl = _custom(f"sgd_ragged_r{rank}", 5, W.ring_edges(5), 1 / 3, SHAPES_RAGGED, rank, steps)
+    _check_sgd(wl, [0.1], TOL_1)
+    _check_sgd(wl, [0.05, 0.02, 0.01], TOL_10)
+
+
+def test_sgd_step_torus_sixteen_columns_and_isolated_worker():
+    wl = _custom("sgd_torus", 9, W.torus_edges(3, 3), 1 / 5, [(200, 650), (33, 12), (40, 1)], 4, 1)
+    _check_sgd(wl, [0.1, 0.1], TOL_10)
+    edges = [[0, 1], [2, 0], [0, 3], [3, 1]]          # worker 4 has no edge: plain SGD for it
+    wl = _custom("sgd_irregular", 5, edges, [0.3, 0.2, 0.25, 0.4], [(48, 36), (17, 1), (20, 64)], 2, 1)
+    _check_sgd(wl, [0.1, 0.2], TOL_10)
+
+
+def test_sgd_step_without_any_edge_is_plain_sgd():
+    from paper_2008_01425_amd.device import GossipBuffers
+    gb = GossipBuffers(2, np.zeros((0, 2), np.int32), np.zeros((0,), np.float32), [(8, 4), (5, 1)], 1, 1)
+    gb.alloc_grads()
+    rng = np.random.default_rng(3)
+    xs = [[rng.standard_normal(s).astype(np.float32) for s in gb.shapes] for _ in range(2)]
+    gs = [[rng.standard_normal(s).astype(np.float32) for s in gb.shapes] for _ in range(2)]
+    for i in range(2):
+        for l in range(2):
+            gb.set_layer(i, l, xs[i][l]); gb.set_grad_layer(i, l, gs[i][l])
+    gb.round_sgd(0.25)
+    for i in range(2):
+        for l in range(2):
+            want = (xs[i][l].astype(np.float64) - 0.25 * gs[i][l].astype(np.float64)).astype(np.float32)
+            assert np.array_equal(gb.get_layer(i, l), want)
+    gb.close()
+
+
+def test_sgd_step_vgg16_full_size_sampled_layers():
+    wl = W.get("vgg16_r1")
+    from oracle import pg_oracle as O
+    from parity_util import oracle_rounds
+    layers = [0, 5, 13]
+    gb = _gb(wl, layers)
+    gb.alloc_grads()
+    X, Q = wl.all_params(layers), wl.all_q(layers)
+    rng = np.random.default_rng(5)
+    G = [[rng.standard_normal(wl.shapes[l]).astype(np.float32) for l in layers] for _ in range(wl.n_workers)]
+    for i in range(wl.n_workers):
+        for j, l in enumerate(layers):
+            gb.set_grad_layer(i, l, G[i][j])
+    gb.round_sgd(0.01)
+    sub = O.Problem(wl.n_workers, wl.edges, wl.edge_w.astype(np.float64), [wl.shapes[l] for l in layers], 1, 1)
+    O.gossip_round(sub, X, Q, G=G, eta=float(np.float32(0.01)))
+    compare_state(gb, X, Q, layers, TOL_1, what="sgd vgg16")
+    gb.close()
+
+
 # ------------------------------------------------------------------ degenerate cases
 def test_identical_workers_are_a_fixed_point():
     from paper_2008_01425_amd.device import GossipBuffers

@@ -117,6 +117,19 @@ def main():
     k_fused = profile(lambda: gb.run(Kp))
     k_unfused = profile(lambda: [gb.round() for _ in range(Kp)])
 
+    # ---- Algorithm 1's step: the same round with the gradient term fused into the update ----
+    gb.alloc_grads()
+    for g in gb.g:
+        g.normal_(0.0, 1e-3)
+    gb.round_sgd(0.1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(Kp):
+        gb.round_sgd(0.1)
+    torch.cuda.synchronize()
+    dt_sgd = time.perf_counter() - t0
+    k_sgd = profile(lambda: [gb.round_sgd(0.1) for _ in range(Kp)])
+
     # the dominant kernel of the timed (fused) pipeline
     dom = max(k_fused.items(), key=lambda kv: kv[1]["total_ms"])
     roofline = {"bound": "hbm", "kernel": dom[0], "achieved": dom[1]["GBps"], "peak": HBM_PEAK_GBS,
@@ -150,6 +163,9 @@ def main():
         "pg_round_unfused": {"rounds_per_s": K / dt_unfused, "ms_per_step": dt_unfused * 1e3 / K,
                              "GBps": bytes_unfused / (dt_unfused / K) / 1e9,
                              "bytes_per_param_per_round": bytes_unfused / (wl.n_workers * wl.params_per_worker)},
+        "pg_round_sgd": {"rounds_per_s": Kp / dt_sgd, "ms_per_step": dt_sgd * 1e3 / Kp,
+                         "bytes_per_param_per_round": (bytes_unfused / (wl.n_workers * wl.params_per_worker)) + 4,
+                         "update_sgd_kernel": k_sgd.get("update_sgd")},
         "roofline": roofline,
         "kernels_fused": k_fused,
         "kernels_unfused": k_unfused,

@@ -243,3 +243,125 @@ int pgo_round_layer(int n_workers, int n_edges, const int32_t *edges, const doub
     return pgo_round_layer_sgd(n_workers, n_edges, edges, edge_w, p, q, rank, power_steps,
                                X, Q, Phat, degenerate, NULL, 0.0);
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Algorithm 2 taken literally: `iterations` single mat-vec iterations, numbered k_done + 1 ...
+ * k_done + iterations, on the unchanged parameters; the approximation of the LAST one is applied
+ * (the procedure overwrites its approximation in the loop and returns it once).
+ *   odd k : vhat = v / |v| in R^q;  p = X_a vhat - X_b vhat;  approximation p vhat^T;  v <- p
+ *   even k: the same with X transposed: vhat = v / |v| in R^p;  p' = X_a^T vhat - X_b^T vhat;
+ *           approximation vhat p'^T;  v <- p'
+ * The vector therefore alternates between R^q and R^p; it is kept in two buffers, Vq (r columns
+ * of length q) and Vp (r columns of length p): the one of the current space is read, the other is
+ * written.  rank > 1 replaces the normalisation by the same Gram-Schmidt as above.  A column
+ * whose normalisation fails (the dropped-column rule above) contributes nothing in that
+ * iteration and leaves the buffer it would have written untouched.
+ * With (k_done even, iterations = 2) this applies exactly the approximation of one power step.
+ * G, eta: optional gradient term of Algorithm 1, as above.
+ * ------------------------------------------------------------------------------------------ */
+static void orthonormalise_cols(const real_t *V, int len, int r, double *work, real_t *U, int32_t *dropped)
+{
+    for (int k = 0; k < r; ++k)
+        for (int t = 0; t < len; ++t) work[(size_t)k * len + t] = (double)V[(size_t)k * len + t];
+    for (int k = 0; k < r; ++k) {
+        double *col = work + (size_t)k * len;
+        double norm2_in = 0.0;
+        for (int t = 0; t < len; ++t) norm2_in += col[t] * col[t];
+        for (int j = 0; j < k; ++j) {
+            const double *prev = work + (size_t)j * len;
+            double dot = 0.0;
+            for (int t = 0; t < len; ++t) dot += prev[t] * col[t];
+            for (int t = 0; t < len; ++t) col[t] -= dot * prev[t];
+        }
+        double norm2 = 0.0;
+        for (int t = 0; t < len; ++t) norm2 += col[t] * col[t];
+        double floor2 = 1e-10 * norm2_in;
+        if (floor2 < (double)FLT_MIN) floor2 = (double)FLT_MIN;
+        int is_drop = !(norm2 >= floor2);
+        dropped[k] = is_drop;
+        double nrm = sqrt(norm2);
+        for (int t = 0; t < len; ++t) col[t] = is_drop ? 0.0 : col[t] / nrm;
+        for (int t = 0; t < len; ++t) U[(size_t)k * len + t] = (real_t)col[t];
+    }
+}
+
+int pgo_alg2_layer(int n_workers, int n_edges, const int32_t *edges, const double *edge_w,
+                   int p, int q, int rank, long long k_done, int iterations,
+                   real_t *const *X, real_t *const *Vq, real_t *const *Vp, int32_t *dropped_out,
+                   const real_t *const *G, double eta)
+{
+    if (n_workers < 1 || n_edges < 0 || p < 1 || q < 1 || rank < 1 || iterations < 1 || k_done < 0)
+        return PGO_ERR_ARG;
+    int r = rank;
+    if (r > p) r = p;
+    if (r > q) r = q;
+    const size_t pq = (size_t)p * q;
+    const int mx = p > q ? p : q;
+    double *ya = malloc(sizeof(double) * mx), *yb = malloc(sizeof(double) * mx);
+    double *work = malloc(sizeof(double) * (size_t)mx * r);
+    real_t *U = malloc(sizeof(real_t) * (size_t)n_edges * mx * r + 8); /* unit vectors of the last iteration */
+    int32_t *drop = malloc(sizeof(int32_t) * (size_t)n_edges * r + 4);
+    double *dX = malloc(sizeof(double) * pq);
+    if (!ya || !yb || !work || !U || !drop || !dX) {
+        free(ya); free(yb); free(work); free(U); free(drop); free(dX);
+        return PGO_ERR_NOMEM;
+    }
+    int last_odd = 0;
+    for (int it = 1; it <= iterations; ++it) {
+        const long long k = k_done + it;
+        last_odd = (int)(k & 1);
+        for (int e = 0; e < n_edges; ++e) {
+            const real_t *Xa = X[edges[2 * e]], *Xb = X[edges[2 * e + 1]];
+            real_t *Ue = U + (size_t)e * mx * r;
+            int32_t *de = drop + (size_t)e * r;
+            if (last_odd) {
+                orthonormalise_cols(Vq[e], q, r, work, Ue, de);
+                for (int c = 0; c < r; ++c) {
+                    if (de[c]) continue;
+                    mat_vec(Xa, p, q, Ue + (size_t)c * q, ya);
+                    mat_vec(Xb, p, q, Ue + (size_t)c * q, yb);
+                    for (int row = 0; row < p; ++row) Vp[e][(size_t)c * p + row] = (real_t)(ya[row] - yb[row]);
+                }
+            } else {
+                orthonormalise_cols(Vp[e], p, r, work, Ue, de);
+                for (int c = 0; c < r; ++c) {
+                    if (de[c]) continue;
+                    mat_t_vec(Xa, p, q, Ue + (size_t)c * p, ya);
+                    mat_t_vec(Xb, p, q, Ue + (size_t)c * p, yb);
+                    for (int t = 0; t < q; ++t) Vq[e][(size_t)c * q + t] = (real_t)(ya[t] - yb[t]);
+                }
+            }
+        }
+    }
+    for (int i = 0; i < n_workers; ++i) {
+        for (size_t t = 0; t < pq; ++t) dX[t] = 0.0;
+        int touched = 0;
+        for (int e = 0; e < n_edges; ++e) {
+            double sign;
+            if (edges[2 * e] == i) sign = -1.0;
+            else if (edges[2 * e + 1] == i) sign = 1.0;
+            else continue;
+            touched = 1;
+            const real_t *Ue = U + (size_t)e * mx * r;
+            for (int c = 0; c < r; ++c) {
+                if (drop[(size_t)e * r + c]) continue;
+                /* odd: (D vhat) vhat^T = Vp Uq^T ; even: vhat (D^T vhat)^T = Up Vq^T */
+                const real_t *left = last_odd ? Vp[e] + (size_t)c * p : Ue + (size_t)c * p;
+                const real_t *right = last_odd ? Ue + (size_t)c * q : Vq[e] + (size_t)c * q;
+                for (int row = 0; row < p; ++row) {
+                    double su = sign * edge_w[e] * (double)left[row];
+                    for (int t = 0; t < q; ++t) dX[(size_t)row * q + t] += su * (double)right[t];
+                }
+            }
+        }
+        if (G && G[i]) {
+            for (size_t t = 0; t < pq; ++t) dX[t] -= eta * (double)G[i][t];
+            touched = 1;
+        }
+        if (touched)
+            for (size_t t = 0; t < pq; ++t) X[i][t] = (real_t)((double)X[i][t] + dX[t]);
+    }
+    if (dropped_out) memcpy(dropped_out, drop, sizeof(int32_t) * (size_t)n_edges * r);
+    free(ya); free(yb); free(work); free(U); free(drop); free(dX);
+    return PGO_OK;
+}

@@ -54,6 +54,12 @@ def _lib(kind: str):
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.pgo_round_layer_sgd.restype = ctypes.c_int
         lib.pgo_round_layer_sgd.argtypes = lib.pgo_round_layer.argtypes + [ctypes.c_void_p, ctypes.c_double]
+        lib.pgo_alg2_layer.restype = ctypes.c_int
+        lib.pgo_alg2_layer.argtypes = [
+            ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_longlong, ctypes.c_int,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_double]
         assert lib.pgo_real_bytes() == (4 if kind == "f32" else 8)
         _loaded[kind] = lib
     return _loaded[kind]
@@ -151,3 +157,38 @@ def gossip_round(prob: Problem, X, Q, layers: Optional[Sequence[int]] = None,
         info.phat = [[per_layer_phat[j][e] for j in range(len(per_layer_phat))]
                      for e in range(prob.n_edges)]
     return info
+
+
+def alg2_round(prob: Problem, X, Vq, Vp, k_done: int, iterations: int,
+               layers: Optional[Sequence[int]] = None, G=None, eta: float = 0.0):
+    """Algorithm 2 taken literally: `iterations` single mat-vec iterations (numbered from
+    k_done + 1) on frozen parameters, the last approximation applied.  Vq[e][l] is (r_l, q_l),
+    Vp[e][l] is (r_l, p_l); both are updated in place.  Returns the dropped flags per layer."""
+    ls = range(len(prob.shapes)) if layers is None else layers
+    out = []
+    for l in ls:
+        p, q = prob.shapes[l]
+        r = prob.layer_rank(l)
+        X_l = [X[i][l] for i in range(prob.n_workers)]
+        dt = X_l[0].dtype
+        kind = {np.dtype(np.float32): "f32", np.dtype(np.float64): "f64"}[np.dtype(dt)]
+        vq = [Vq[e][l] for e in range(prob.n_edges)]
+        vp = [Vp[e][l] for e in range(prob.n_edges)]
+        for a in X_l:
+            assert a.dtype == dt and a.shape == (p, q) and a.flags.c_contiguous
+        for a in vq:
+            assert a.dtype == dt and a.shape == (r, q) and a.flags.c_contiguous
+        for a in vp:
+            assert a.dtype == dt and a.shape == (r, p) and a.flags.c_contiguous
+        G_l = None if G is None else [G[i][l] for i in range(prob.n_workers)]
+        drop = np.zeros((prob.n_edges, r), dtype=np.int32)
+        rc = _lib(kind).pgo_alg2_layer(
+            prob.n_workers, prob.n_edges, prob.edges.ctypes.data, prob.edge_w.ctypes.data,
+            p, q, prob.rank, int(k_done), int(iterations),
+            ctypes.cast(_ptr_array(X_l), ctypes.c_void_p), ctypes.cast(_ptr_array(vq), ctypes.c_void_p),
+            ctypes.cast(_ptr_array(vp), ctypes.c_void_p), drop.ctypes.data,
+            ctypes.cast(_ptr_array(G_l), ctypes.c_void_p) if G_l is not None else None, float(eta))
+        if rc != 0:
+            raise ValueError(f"pgo_alg2_layer failed with code {rc}")
+        out.append(drop)
+    return out

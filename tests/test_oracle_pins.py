@@ -484,3 +484,110 @@ def test_zero_gradient_is_the_gossip_round_bitwise():
     O.gossip_round(prob, Xp, Qp)
     for i in range(4):
         assert np.array_equal(X[i][0], Xp[i][0])
+
+
+# ------------------------------------------------ Algorithm 2, one iteration at a time
+def _alg2_state(prob, rng, dtype=np.float64):
+    Vq = [[rng.standard_normal((prob.layer_rank(l), prob.shapes[l][1])).astype(dtype)
+           for l in range(len(prob.shapes))] for _ in range(prob.n_edges)]
+    Vp = [[np.zeros((prob.layer_rank(l), prob.shapes[l][0]), dtype=dtype)
+           for l in range(len(prob.shapes))] for _ in range(prob.n_edges)]
+    return Vq, Vp
+
+
+def test_one_odd_iteration_is_the_right_projection_of_section_3():
+    """Section 3: C_v(X) = (X v) v^T with |v| = 1; Algorithm 2's odd iteration applies
+    (D vhat) vhat^T and stores v <- D vhat in R^p."""
+    rng = np.random.default_rng(40)
+    p, q, w = 7, 5, 0.3
+    prob = make(2, [[0, 1]], w, [(p, q)])
+    X, _ = rand_state(prob, rng)
+    Vq, Vp = _alg2_state(prob, rng)
+    Xa, Xb, v = X[0][0].copy(), X[1][0].copy(), Vq[0][0][0].copy()
+    O.alg2_round(prob, X, Vq, Vp, 0, 1)
+    vh = v / np.linalg.norm(v)
+    D = Xa - Xb
+    assert np.allclose(Vp[0][0][0], D @ vh, atol=1e-14)
+    assert np.array_equal(Vq[0][0][0], v)                       # the R^q buffer is only read
+    assert np.allclose(X[0][0], Xa - w * np.outer(D @ vh, vh), atol=1e-14)
+    assert np.allclose(X[1][0], Xb + w * np.outer(D @ vh, vh), atol=1e-14)
+
+
+def test_one_even_iteration_is_the_left_projection():
+    """Algorithm 2, even iteration ('the same with X transposed'): vhat in R^p, approximation
+    vhat (D^T vhat)^T, v <- D^T vhat in R^q."""
+    rng = np.random.default_rng(41)
+    p, q, w = 6, 8, 0.25
+    prob = make(2, [[0, 1]], w, [(p, q)])
+    X, _ = rand_state(prob, rng)
+    Vq, Vp = _alg2_state(prob, rng)
+    Vp[0][0][0] = rng.standard_normal(p)
+    Xa, Xb, v = X[0][0].copy(), X[1][0].copy(), Vp[0][0][0].copy()
+    O.alg2_round(prob, X, Vq, Vp, 1, 1)                          # k = 2
+    vh = v / np.linalg.norm(v)
+    D = Xa - Xb
+    assert np.allclose(Vq[0][0][0], D.T @ vh, atol=1e-14)
+    assert np.allclose(X[0][0], Xa - w * np.outer(vh, D.T @ vh), atol=1e-14)
+
+
+@pytest.mark.parametrize("rank", [1, 3])
+def test_two_iterations_apply_the_same_approximation_as_one_power_step(rank):
+    """Odd then even iteration on frozen parameters = P, orthonormalise, Q': the paper's
+    'PowerGossip (2 iterations)' is this build's one power step (normalising v first does not
+    change the orthonormalised product)."""
+    rng = np.random.default_rng(42)
+    n = 4
+    prob = make(n, ring(n), 1 / 3, [(9, 6), (5, 1)], rank=rank)
+    X, Q = rand_state(prob, rng)
+    X2 = [[a.copy() for a in row] for row in X]
+    Vq = [[a.copy() for a in row] for row in Q]
+    Vp = [[np.zeros((prob.layer_rank(l), prob.shapes[l][0])) for l in range(2)] for _ in range(n)]
+    info = O.gossip_round(prob, X, Q, want_phat=True)
+    O.alg2_round(prob, X2, Vq, Vp, 0, 2)
+    for i in range(n):
+        for l in range(2):
+            assert np.allclose(X2[i][l], X[i][l], atol=1e-12)
+    for e in range(n):
+        for l in range(2):
+            assert np.allclose(Vq[e][l], Q[e][l], atol=1e-12)   # v after the even iteration = Q'
+
+
+def test_iterations_alternate_spaces_and_keep_the_mean():
+    """Algorithm 2: v 'changes between R^p and R^q'; Lemma 1 holds for every iteration count."""
+    rng = np.random.default_rng(43)
+    n = 5
+    prob = make(n, ring(n), 1 / 3, [(8, 5)], rank=2)
+    X, _ = rand_state(prob, rng)
+    Vq, Vp = _alg2_state(prob, rng)
+    mean0 = sum(X[i][0] for i in range(n)) / n
+    k = 0
+    for its in (1, 1, 3, 2):
+        vq0 = [Vq[e][0].copy() for e in range(n)]
+        vp0 = [Vp[e][0].copy() for e in range(n)]
+        O.alg2_round(prob, X, Vq, Vp, k, its)
+        k += its
+        if its == 1:      # exactly one buffer was written, the other only read
+            wrote_p = any(not np.array_equal(Vp[e][0], vp0[e]) for e in range(n))
+            wrote_q = any(not np.array_equal(Vq[e][0], vq0[e]) for e in range(n))
+            assert wrote_p != wrote_q and wrote_p == (k % 2 == 1)
+        assert np.allclose(sum(X[i][0] for i in range(n)) / n, mean0, atol=1e-13)
+
+
+def test_iterated_single_steps_reach_the_top_singular_pair():
+    """Eq. (3) as written: alternating single iterations on a fixed difference are power iteration."""
+    rng = np.random.default_rng(44)
+    p, q = 10, 7
+    U, _ = np.linalg.qr(rng.standard_normal((p, p)))
+    V, _ = np.linalg.qr(rng.standard_normal((q, q)))
+    sv = np.array([4.0, 1.0, 0.5, 0.2, 0.1, 0.05, 0.01])
+    D = (U[:, :q] * sv) @ V.T
+    prob = make(2, [[0, 1]], 0.0, [(p, q)])
+    X = [[D.copy()], [np.zeros((p, q))]]
+    Vq, Vp = _alg2_state(prob, rng)
+    for k in range(40):
+        O.alg2_round(prob, X, Vq, Vp, k, 1)
+    Us, ss, Vts = np.linalg.svd(D)
+    s1 = np.sign(Vp[0][0][0] @ Us[:, 0])
+    assert np.allclose(Vp[0][0][0], s1 * ss[0] * Us[:, 0], atol=1e-8) or \
+        np.allclose(np.linalg.norm(Vp[0][0][0]), ss[0], atol=1e-8)
+    assert abs(np.linalg.norm(Vq[0][0][0]) - ss[0]) < 1e-8

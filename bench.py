@@ -130,6 +130,17 @@ def main():
     dt_sgd = time.perf_counter() - t0
     k_sgd = profile(lambda: [gb.round_sgd(0.1) for _ in range(Kp)])
 
+    # ---- Algorithm 2 one iteration per call (the paper's "1 iteration" setting), with gradient
+    gb.alloc_pstate()
+    gb.iterate(0, 1, 0.1)
+    gb.iterate(1, 1, 0.1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(2, 2 + 2 * Kp):
+        gb.iterate(k, 1, 0.1)
+    torch.cuda.synchronize()
+    dt_it = time.perf_counter() - t0
+
     # the dominant kernel of the timed (fused) pipeline
     dom = max(k_fused.items(), key=lambda kv: kv[1]["total_ms"])
     roofline = {"bound": "hbm", "kernel": dom[0], "achieved": dom[1]["GBps"], "peak": HBM_PEAK_GBS,
@@ -166,6 +177,9 @@ def main():
         "pg_round_sgd": {"rounds_per_s": Kp / dt_sgd, "ms_per_step": dt_sgd * 1e3 / Kp,
                          "bytes_per_param_per_round": (bytes_unfused / (wl.n_workers * wl.params_per_worker)) + 4,
                          "update_sgd_kernel": k_sgd.get("update_sgd")},
+        "pg_iterate_1_sgd": {"iterations_per_s": 2 * Kp / dt_it, "ms_per_iteration": dt_it * 1e3 / (2 * Kp),
+                             "bytes_per_param_per_iteration": 16.0,
+                             "GBps": 16.0 * wl.n_workers * wl.params_per_worker / (dt_it / (2 * Kp)) / 1e9},
         "roofline": roofline,
         "kernels_fused": k_fused,
         "kernels_unfused": k_unfused,

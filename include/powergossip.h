@@ -168,6 +168,32 @@ int pg_round_sgd(pg_ctx *ctx, float *const *worker_params, const float *const *w
                  float eta, float *q_state, void *workspace, void *hip_stream);
 
 /*
+ * Algorithm 2 taken literally, one mat-vec iteration at a time.  `iterations` iterations,
+ * numbered k_done + 1 ... k_done + iterations, run on the unchanged parameters and the
+ * approximation of the LAST one is applied (the procedure overwrites its approximation in the
+ * loop and returns it once); with `worker_grads` the step is line 6 of Algorithm 1.
+ *   odd k : vhat = v / |v| in R^q;  p  = X_a vhat - X_b vhat;      approximation p vhat^T;   v <- p
+ *   even k: vhat = v / |v| in R^p;  p' = X_a^T vhat - X_b^T vhat;  approximation vhat p'^T;  v <- p'
+ * The vector alternates between the two spaces: in R^q it lives in q_state (layout above), in
+ * R^p in p_state: pg_pstate_floats floats, the block of edge e, layer l at float pg_p_offset(e, l)
+ * (a multiple of 4), r_l columns of p_l floats.  The space of the current iteration is read, the
+ * other written; the caller keeps k (pass the number of iterations already done) and both
+ * buffers.  rank > 1 (at most 8 here) orthonormalises the r columns instead of normalising one.
+ * A column whose normalisation fails by the dropped-column rule contributes nothing and leaves
+ * the buffer it would have written untouched.  One iteration sends one vector per matrix --
+ * the paper's "PowerGossip (1 iteration)"; k_done even with iterations = 2 applies the same
+ * approximation as one power step of pg_round.
+ *   p_state        device, 16-byte aligned, in/out
+ *   worker_grads   NULL, or as in pg_round_sgd;  eta ignored when NULL
+ * Other arguments and errors as pg_round.
+ */
+size_t pg_pstate_floats(const pg_ctx *ctx);
+size_t pg_p_offset(const pg_ctx *ctx, int edge, int layer);
+int pg_iterate(pg_ctx *ctx, float *const *worker_params, float *q_state, float *p_state,
+               long long k_done, int iterations, const float *const *worker_grads, float eta,
+               void *workspace, void *hip_stream);
+
+/*
  * `rounds` consecutive gossip rounds with nothing touching the parameters in between
  * (the pure consensus iteration, Eq. (4)).  Same result as calling pg_round `rounds` times;
  * the update of round t and the first product of round t+1 share one pass over the
@@ -182,7 +208,8 @@ int pg_run(pg_ctx *ctx, float *const *worker_params, float *q_state, void *works
  * adds them up per kernel kind since the previous collect, and clears the record.
  */
 typedef struct pg_kernel_time {
-    char name[32];   /* "sweep_p", "orth_p", "sweep_q", "combine_q", "update", "update_sweep_p", "update_sgd" */
+    char name[32];   /* "sweep_p", "orth_p", "sweep_q", "combine_q", "update", "update_sweep_p", "update_sgd",
+                        "orth_v", "combine_p" */
     int launches;    /* kernel launches of this kind */
     double ms;       /* summed duration */
     double bytes;    /* summed algorithmic bytes of parameter traffic (4 B per element read or written) */

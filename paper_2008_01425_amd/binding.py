@@ -18,7 +18,7 @@ EXPORTS = [
     "pg_strerror", "pg_init", "pg_destroy", "pg_param_floats", "pg_layer_offset", "pg_layer_rank",
     "pg_qstate_floats", "pg_q_offset", "pg_workspace_bytes", "pg_ws_phat_offset",
     "pg_ws_flag_offset", "pg_message_floats", "pg_round_bytes", "pg_upload", "pg_round", "pg_round_sgd",
-    "pg_run",
+    "pg_run", "pg_iterate", "pg_pstate_floats", "pg_p_offset",
     "pg_profile_enable", "pg_profile_collect",
 ]
 
@@ -56,6 +56,12 @@ def _load():
     lib.pg_round.argtypes = [vp, vp, vp, vp, vp]
     lib.pg_round_sgd.restype = ci
     lib.pg_round_sgd.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp]
+    lib.pg_pstate_floats.restype = sz
+    lib.pg_pstate_floats.argtypes = [vp]
+    lib.pg_p_offset.restype = sz
+    lib.pg_p_offset.argtypes = [vp, ci, ci]
+    lib.pg_iterate.restype = ci
+    lib.pg_iterate.argtypes = [vp, vp, vp, vp, ctypes.c_longlong, ci, vp, ctypes.c_float, vp, vp]
     lib.pg_run.restype = ci
     lib.pg_run.argtypes = [vp, vp, vp, vp, vp, ci]
     lib.pg_profile_enable.restype = ci
@@ -132,6 +138,17 @@ def pg_round_sgd(ctx, worker_ptrs: Sequence[int], grad_ptrs: Sequence[int], eta:
                  ws_ptr: int, stream: int = 0) -> None:
     """grad_ptrs: device addresses of the n gradient buffers (laid out like the parameters)."""
     _check(lib.pg_round_sgd(ctx, _ptr_table(worker_ptrs), _ptr_table(grad_ptrs), eta, q_ptr, ws_ptr, stream))
+
+
+def pg_pstate_floats(ctx): return lib.pg_pstate_floats(ctx)
+def pg_p_offset(ctx, edge, layer): return lib.pg_p_offset(ctx, edge, layer)
+
+
+def pg_iterate(ctx, worker_ptrs: Sequence[int], q_ptr: int, p_ptr: int, k_done: int, iterations: int,
+               grad_ptrs, eta: float, ws_ptr: int, stream: int = 0) -> None:
+    """`iterations` of Algorithm 2's single iterations, numbered from k_done + 1; grad_ptrs None = no gradient."""
+    _check(lib.pg_iterate(ctx, _ptr_table(worker_ptrs), q_ptr, p_ptr, k_done, iterations,
+                          None if grad_ptrs is None else _ptr_table(grad_ptrs), eta, ws_ptr, stream))
 
 
 def pg_run(ctx, worker_ptrs: Sequence[int], q_ptr: int, ws_ptr: int, stream: int, rounds: int) -> None:

@@ -17,9 +17,10 @@ namespace {
 
 constexpr int kOrthThreads = 1024;
 
-enum Kind { K_SWEEP_P = 0, K_ORTH_P, K_SWEEP_Q, K_COMBINE_Q, K_UPDATE, K_UPDATE_SWEEP_P, K_UPDATE_SGD, K_COUNT };
-const char *const kKindName[K_COUNT] = {"sweep_p", "orth_p",  "sweep_q", "combine_q",
-                                        "update",  "update_sweep_p", "update_sgd"};
+enum Kind { K_SWEEP_P = 0, K_ORTH_P, K_SWEEP_Q, K_COMBINE_Q, K_UPDATE, K_UPDATE_SWEEP_P, K_UPDATE_SGD,
+            K_ORTH_V, K_COMBINE_P, K_COUNT };
+const char *const kKindName[K_COUNT] = {"sweep_p", "orth_p", "sweep_q", "combine_q", "update",
+                                        "update_sweep_p", "update_sgd", "orth_v", "combine_p"};
 
 struct ProfRec {
     int kind;
@@ -102,8 +103,16 @@ struct Launcher {
     hipStream_t st;
     float *qstate;
     char *ws;
-    double eta = 0.0;  // learning rate of the fused gradient term (pg_round_sgd only)
+    double eta = 0.0;  // learning rate of the fused gradient term
+    // Algorithm 2 one iteration at a time: the right-hand vectors (length q) and the left-hand
+    // vectors (length p) the sweeps and the update read, when they are not the state / Phat
+    const float *rhs = nullptr;
+    const float *lhs = nullptr;
     int status = PG_OK;
+
+    const float *right() const { return rhs ? rhs : qstate; }
+    const float *left() const { return lhs ? lhs : ph(); }
+    float *uq() const { return (float *)(ws + c->plan.ws_uq); }
 
     double *pw() const { return (double *)(ws + c->plan.ws_pw); }
     double *qw() const { return (double *)(ws + c->plan.ws_qw); }
@@ -145,13 +154,13 @@ struct Launcher {
             // the gradient slice is prefetched like X: halve the row blocking to stay in registers
             constexpr int M = (RC <= 2) ? (GRAD ? 4 : 8) : 4;
             row_kernel<RC, M, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
-                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, qstate, ph(), pw(), c->d_gs, eta);
+                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
         } else {
             // register budget: RC accumulators and RC update coefficients per row
             constexpr int M = ((UPD && SWP) || GRAD) ? 2 : 4;
             size_t lds = (size_t)RC * rc.max_seg * sizeof(float);
             row_wide_kernel<RC, M, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>(
-                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, qstate, ph(), pw(), c->d_gs, eta);
+                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
         }
     }
     template <int RC>
@@ -214,7 +223,7 @@ struct Launcher {
                               (size_t)(kThreads / 64 - 1) * 64 * 4 * sizeof(double));
         col_kernel<RC, U><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>(
             c->d_col_tiles + cc.dev_first, n, /*reverse=*/c->col_reverse, c->d_pairs, c->d_cols,
-            c->d_xs, ph(), qw());
+            c->d_xs, left(), qw());
     }
     // The Q-sweep walks the parameters back to front: it starts on what the pass before it
     // (always a front-to-back row pass) touched last.
@@ -259,6 +268,32 @@ struct Launcher {
         else if (rmax <= 8) small ? orth_launch<256, 8>() : orth_launch<512, 8>();
         else orth_kernel<kOrthThreads><<<dim3((unsigned)c->plan.els.size()), dim3(kOrthThreads), 0, st>>>(
             c->d_els, pw(), pdb(), ph(), flags());
+        check();
+        end();
+    }
+    // Algorithm 2's normalisation of the stored vectors (Gram-Schmidt for r > 1): src -> dst.
+    template <int RMAX>
+    void orth_v_launch(const float *src, float *dst, int in_q) {
+        constexpr int NT = RMAX <= 4 ? 1024 : 512;
+        orth_state_kernel<NT, RMAX><<<dim3((unsigned)c->plan.els.size()), dim3(NT), 0, st>>>(
+            c->d_els, src, dst, in_q, flags());
+    }
+    void orth_v(const float *src, float *dst, int in_q) {
+        if (status || c->plan.els.empty()) return;
+        begin(K_ORTH_V, 0.0);
+        const int rmax = c->plan.max_layer_rank;
+        if (rmax <= 1) orth_v_launch<1>(src, dst, in_q);
+        else if (rmax <= 2) orth_v_launch<2>(src, dst, in_q);
+        else if (rmax <= 4) orth_v_launch<4>(src, dst, in_q);
+        else if (rmax <= 8) orth_v_launch<8>(src, dst, in_q);
+        else status = PG_ERR_ARG;
+        check();
+        end();
+    }
+    void combine_p(float *pstate) {
+        if (status || c->plan.els.empty()) return;
+        begin(K_COMBINE_P, 0.0);
+        comb_p_kernel<<<dim3((unsigned)c->plan.els.size()), dim3(kThreads), 0, st>>>(c->d_els, pw(), flags(), pstate);
         check();
         end();
     }
@@ -406,6 +441,11 @@ size_t pg_q_offset(const pg_ctx *c, int e, int l) {
     if (!c || l < 0 || l >= c->plan.n_layers || e < 0 || e >= c->plan.n_edges) return (size_t)-1;
     return (size_t)c->plan.q_off[(size_t)e * c->plan.n_layers + l];
 }
+size_t pg_pstate_floats(const pg_ctx *c) { return c ? c->plan.pstate_floats : (size_t)-1; }
+size_t pg_p_offset(const pg_ctx *c, int e, int l) {
+    if (!c || l < 0 || l >= c->plan.n_layers || e < 0 || e >= c->plan.n_edges) return (size_t)-1;
+    return (size_t)c->plan.ph_off[(size_t)e * c->plan.n_layers + l];
+}
 size_t pg_workspace_bytes(const pg_ctx *c) { return c ? c->plan.ws_bytes : (size_t)-1; }
 size_t pg_ws_phat_offset(const pg_ctx *c, int e, int l) {
     if (!c || l < 0 || l >= c->plan.n_layers || e < 0 || e >= c->plan.n_edges) return (size_t)-1;
@@ -451,6 +491,42 @@ int pg_round_sgd(pg_ctx *c, float *const *worker_params, const float *const *wor
         L.rows(true, false, /*grad=*/true);
     }
     L.sgd_isolated();
+    return L.status;
+}
+
+int pg_iterate(pg_ctx *c, float *const *worker_params, float *q_state, float *p_state, long long k_done,
+               int iterations, const float *const *worker_grads, float eta, void *workspace,
+               void *hip_stream) {
+    hipStream_t st = (hipStream_t)hip_stream;
+    int rc = prepare(c, worker_params, q_state, workspace, st);
+    if (rc) return rc;
+    if (k_done < 0 || iterations < 1 || !(eta == eta)) return PG_ERR_ARG;
+    if (c->plan.pstate_floats > 0 && (!p_state || ((uintptr_t)p_state & 15))) return PG_ERR_ARG;
+    if (c->plan.max_layer_rank > 8) return PG_ERR_ARG;
+    if (worker_grads && (rc = prepare_grads(c, worker_grads, st))) return rc;
+    Launcher L{c, st, q_state, (char *)workspace};
+    L.eta = (double)eta;
+    if (c->plan.n_edges > 0) {
+        for (int it = 1; it <= iterations; ++it) {
+            if ((k_done + it) & 1) {
+                // odd: vhat = v / |v| in R^q, p = X_a vhat - X_b vhat, v <- p (in R^p)
+                L.orth_v(q_state, L.uq(), 1);
+                L.rhs = L.uq();
+                L.rows(false, true);
+                L.combine_p(p_state);
+                L.lhs = p_state;  // approximation p vhat^T
+            } else {
+                // even: vhat = v / |v| in R^p, p' = X_a^T vhat - X_b^T vhat, v <- p' (in R^q)
+                L.orth_v(p_state, L.ph(), 0);
+                L.lhs = nullptr;  // the unit vectors sit where Phat sits
+                L.sweep_q();
+                L.combine_q();
+                L.rhs = nullptr;  // approximation vhat p'^T
+            }
+        }
+        L.rows(true, false, worker_grads != nullptr);
+    }
+    if (worker_grads) L.sgd_isolated();
     return L.status;
 }
 

@@ -671,16 +671,34 @@ orth_kernel(const EdgeLayerDesc *__restrict__ els, const double *__restrict__ pw
 // R_kk the norm of its residual, so the dropped-column test reads d_k = G_kk - sum_j R_jk^2
 // against max(FLT_MIN, 1e-10 G_kk)); pass 2 applies Phat = P R^-1 row by row by forward
 // substitution.  Same columns as the left-to-right Gram-Schmidt up to rounding in double.
+// What is orthonormalised and where the result goes: either the difference of the two workers'
+// partial products (P = sum Pw_a - sum Pw_b, `st` null), or r stored float columns of `len`
+// entries (one of Algorithm 2's vectors v_ij per column).
+struct GramIO {
+    const double *pw;
+    const float *st;
+    int64_t st_off;
+    int len;
+    float *out;
+    int64_t out_off;
+};
+
 template <int RMAX>
-__device__ __forceinline__ void gram_load_row(const EdgeLayerDesc &d, const double *__restrict__ pw,
-                                              int row, double (&v)[RMAX]) {
+__device__ __forceinline__ void gram_load_row(const EdgeLayerDesc &d, const GramIO &io, int row,
+                                              double (&v)[RMAX]) {
+    if (io.st) {
+#pragma unroll
+        for (int k = 0; k < RMAX; ++k)
+            v[k] = (k < d.r) ? (double)io.st[io.st_off + (int64_t)k * io.len + row] : 0.0;
+        return;
+    }
 #pragma unroll
     for (int k = 0; k < RMAX; ++k) {
         double sa = 0.0, sb = 0.0;
         if (k < d.r) {
             for (int s = 0; s < d.nseg; ++s) {
-                sa += pw[d.pwa_off + s * d.pwa_seg + (int64_t)k * d.p + row];
-                sb += pw[d.pwb_off + s * d.pwb_seg + (int64_t)k * d.p + row];
+                sa += io.pw[d.pwa_off + s * d.pwa_seg + (int64_t)k * d.p + row];
+                sb += io.pw[d.pwb_off + s * d.pwb_seg + (int64_t)k * d.p + row];
             }
         }
         v[k] = sa - sb;
@@ -690,7 +708,7 @@ __device__ __forceinline__ void gram_load_row(const EdgeLayerDesc &d, const doub
 // Pass 1 over rows [row0, row1): the work-group's Gram sums, packed G[j][k] (j <= k) at
 // k (k + 1) / 2 + j, left in sG.
 template <int NT, int RMAX>
-__device__ __forceinline__ void gram_rows(const EdgeLayerDesc &d, const double *__restrict__ pw,
+__device__ __forceinline__ void gram_rows(const EdgeLayerDesc &d, const GramIO &io,
                                           int row0, int row1,
                                           double (*sRed)[RMAX * (RMAX + 1) / 2], double *sG) {
     constexpr int NG = RMAX * (RMAX + 1) / 2;
@@ -701,7 +719,7 @@ __device__ __forceinline__ void gram_rows(const EdgeLayerDesc &d, const double *
 #pragma unroll 2
     for (int row = row0 + tid; row < row1; row += NT) {
         double v[RMAX];
-        gram_load_row<RMAX>(d, pw, row, v);
+        gram_load_row<RMAX>(d, io, row, v);
         int idx = 0;
 #pragma unroll
         for (int k = 0; k < RMAX; ++k)
@@ -758,13 +776,13 @@ __device__ __forceinline__ void gram_factor(const EdgeLayerDesc &d, const double
 
 // Pass 2 over rows [row0, row1): Phat = P R^-1 by forward substitution, rounded to float.
 template <int NT, int RMAX>
-__device__ __forceinline__ void gram_apply_rows(const EdgeLayerDesc &d, const double *__restrict__ pw,
-                                                float *__restrict__ phat, int row0, int row1,
+__device__ __forceinline__ void gram_apply_rows(const EdgeLayerDesc &d, const GramIO &io,
+                                                int row0, int row1,
                                                 const double (*sR)[RMAX], const int *sDrop) {
 #pragma unroll 2
     for (int row = row0 + (int)threadIdx.x; row < row1; row += NT) {
         double v[RMAX], ph[RMAX];
-        gram_load_row<RMAX>(d, pw, row, v);
+        gram_load_row<RMAX>(d, io, row, v);
 #pragma unroll
         for (int k = 0; k < RMAX; ++k) {
             if (k < d.r) {
@@ -772,7 +790,7 @@ __device__ __forceinline__ void gram_apply_rows(const EdgeLayerDesc &d, const do
 #pragma unroll
                 for (int j = 0; j < k; ++j) t -= sR[j][k] * ph[j];
                 ph[k] = sDrop[k] ? 0.0 : t / sR[k][k];
-                phat[d.ph_off + (int64_t)k * d.p + row] = (float)ph[k];
+                io.out[io.out_off + (int64_t)k * io.len + row] = (float)ph[k];
             } else {
                 ph[k] = 0.0;
             }
@@ -791,9 +809,51 @@ orth_gram_kernel(const EdgeLayerDesc *__restrict__ els, const double *__restrict
     __shared__ double sR[RMAX][RMAX];
     __shared__ int sDrop[RMAX];
     const EdgeLayerDesc d = els[blockIdx.x];
-    gram_rows<NT, RMAX>(d, pw, 0, d.p, sRed, sG);
+    const GramIO io{pw, nullptr, 0, d.p, phat, d.ph_off};
+    gram_rows<NT, RMAX>(d, io, 0, d.p, sRed, sG);
     gram_factor<RMAX>(d, sG, sR, sDrop, flags, true);
-    gram_apply_rows<NT, RMAX>(d, pw, phat, 0, d.p, sR, sDrop);
+    gram_apply_rows<NT, RMAX>(d, io, 0, d.p, sR, sDrop);
+}
+
+// Orthonormalise the r stored columns of every (edge, layer) -- Algorithm 2's vhat = v / |v|,
+// Gram-Schmidt for r > 1 -- from `src` into `dst` (same offsets).  in_q = 1: the vectors live
+// in R^q (state layout), 0: in R^p (Phat layout).
+template <int NT, int RMAX>
+__global__ void __launch_bounds__(NT)
+orth_state_kernel(const EdgeLayerDesc *__restrict__ els, const float *__restrict__ src,
+                  float *__restrict__ dst, int in_q, int32_t *__restrict__ flags) {
+    constexpr int NG = RMAX * (RMAX + 1) / 2;
+    __shared__ double sRed[NT / 64][NG];
+    __shared__ double sG[NG];
+    __shared__ double sR[RMAX][RMAX];
+    __shared__ int sDrop[RMAX];
+    const EdgeLayerDesc d = els[blockIdx.x];
+    const int len = in_q ? d.q : d.p;
+    const int64_t off = in_q ? d.q_off : d.ph_off;
+    const GramIO io{nullptr, src, off, len, dst, off};
+    gram_rows<NT, RMAX>(d, io, 0, len, sRed, sG);
+    gram_factor<RMAX>(d, sG, sR, sDrop, flags, true);
+    gram_apply_rows<NT, RMAX>(d, io, 0, len, sR, sDrop);
+}
+
+// Algorithm 2, odd iteration: v_ij <- p_j - p_i, the difference of the two workers' products,
+// stored unnormalised as float columns of length p; columns whose unit vector was dropped keep
+// their old content.
+__global__ void __launch_bounds__(kThreads)
+comb_p_kernel(const EdgeLayerDesc *__restrict__ els, const double *__restrict__ pw,
+              const int32_t *__restrict__ flags, float *__restrict__ pstate) {
+    const EdgeLayerDesc d = els[blockIdx.x];
+    for (int k = 0; k < d.r; ++k) {
+        if (flags[d.flag_off + k]) continue;
+        for (int row = threadIdx.x; row < d.p; row += kThreads) {
+            double sa = 0.0, sb = 0.0;
+            for (int s = 0; s < d.nseg; ++s) {
+                sa += pw[d.pwa_off + s * d.pwa_seg + (int64_t)k * d.p + row];
+                sb += pw[d.pwb_off + s * d.pwb_seg + (int64_t)k * d.p + row];
+            }
+            pstate[d.ph_off + (int64_t)k * d.p + row] = (float)(sa - sb);
+        }
+    }
 }
 
 // Tall layers: the rows of an (edge, layer) are cut into chunks, one work-group each.  The first
@@ -808,7 +868,8 @@ orth_gram_part_kernel(const OrthTile *__restrict__ tiles, const EdgeLayerDesc *_
     __shared__ double sG[NG];
     const OrthTile t = tiles[blockIdx.x];
     const EdgeLayerDesc d = els[t.el];
-    gram_rows<NT, RMAX>(d, pw, t.row0, t.row0 + t.nrows, sRed, sG);
+    const GramIO io{pw, nullptr, 0, d.p, nullptr, 0};
+    gram_rows<NT, RMAX>(d, io, t.row0, t.row0 + t.nrows, sRed, sG);
     if (threadIdx.x < NG) gpart[(int64_t)blockIdx.x * NG + threadIdx.x] = sG[threadIdx.x];
 }
 
@@ -831,7 +892,8 @@ orth_gram_apply_kernel(const OrthTile *__restrict__ tiles, const EdgeLayerDesc *
     }
     __syncthreads();
     gram_factor<RMAX>(d, sG, sR, sDrop, flags, t.chunk == 0);
-    gram_apply_rows<NT, RMAX>(d, pw, phat, t.row0, t.row0 + t.nrows, sR, sDrop);
+    const GramIO io{pw, nullptr, 0, d.p, phat, d.ph_off};
+    gram_apply_rows<NT, RMAX>(d, io, t.row0, t.row0 + t.nrows, sR, sDrop);
 }
 
 // Per (edge, layer): Q' = (sum of worker a's row-block partials) - (worker b's), rounded to

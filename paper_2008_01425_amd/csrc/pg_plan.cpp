@@ -104,6 +104,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             flo += L.r;
         }
     P.qstate_floats = (size_t)qo;
+    P.pstate_floats = (size_t)pho;
 
     // ---- tile sizes: the byte targets suit workloads that fill the chip many times over; small
     // parameter sets are cut finer so that every SIMD still gets a tile ----
@@ -291,6 +292,9 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     }
     P.ws_gpart = o;
     o = (size_t)round_up(o + P.orth_tiles.size() * 36 * 8, 256);
+    // unit vectors in R^q of Algorithm 2's odd iterations (state layout)
+    P.ws_uq = o;
+    o = (size_t)round_up(o + (size_t)qo * 4, 256);
     P.ws_bytes = std::max<size_t>(o, 256);
 
     // ---- tiles, grouped by kernel instantiation, in address order ----

@@ -45,12 +45,12 @@ struct Plan {
     std::vector<LayerInfo> layers;
     std::vector<std::vector<int>> incident;  // per worker: edge ids in edge-list order
 
-    size_t param_floats = 0, qstate_floats = 0, message_floats = 0;
+    size_t param_floats = 0, qstate_floats = 0, pstate_floats = 0, message_floats = 0;
     double elems_per_worker = 0;             // N = sum p*q
     std::vector<int64_t> q_off;              // [e * L + l]
 
     // workspace sections (byte offsets) and their sizes
-    size_t ws_pw = 0, ws_qw = 0, ws_pd = 0, ws_ph = 0, ws_flag = 0, ws_gpart = 0, ws_bytes = 0;
+    size_t ws_pw = 0, ws_qw = 0, ws_pd = 0, ws_ph = 0, ws_flag = 0, ws_gpart = 0, ws_uq = 0, ws_bytes = 0;
     std::vector<int64_t> ph_off;             // [e * L + l] float offset inside the Phat section
     std::vector<int64_t> flag_off;           // [e * L + l] int32 index inside the flag section
 

@@ -104,6 +104,27 @@ class GossipBuffers:
         s = torch.cuda.current_stream(self.device) if stream is None else stream
         B.pg_round_sgd(self.ctx, self.ptrs, self.gptrs, eta, self.q.data_ptr(), self.ws.data_ptr(), s.cuda_stream)
 
+    def alloc_pstate(self):
+        """The R^p half of Algorithm 2's alternating vector (zero-filled)."""
+        self.pstate = torch.zeros(max(1, B.pg_pstate_floats(self.ctx)), dtype=torch.float32, device=self.device)
+
+    def set_p(self, e: int, l: int, a: np.ndarray):
+        r, p = self.ranks[l], self.shapes[l][0]
+        off = B.pg_p_offset(self.ctx, e, l)
+        self.pstate[off:off + r * p].copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32).reshape(-1)))
+
+    def get_p(self, e: int, l: int) -> np.ndarray:
+        r, p = self.ranks[l], self.shapes[l][0]
+        off = B.pg_p_offset(self.ctx, e, l)
+        return self.pstate[off:off + r * p].cpu().numpy().reshape(r, p)
+
+    def iterate(self, k_done: int, iterations: int, eta: Optional[float] = None,
+                stream: Optional[torch.cuda.Stream] = None):
+        s = torch.cuda.current_stream(self.device) if stream is None else stream
+        B.pg_iterate(self.ctx, self.ptrs, self.q.data_ptr(), self.pstate.data_ptr(), k_done, iterations,
+                     None if eta is None else self.gptrs, 0.0 if eta is None else eta,
+                     self.ws.data_ptr(), s.cuda_stream)
+
     def run(self, rounds: int, stream: Optional[torch.cuda.Stream] = None):
         s = torch.cuda.current_stream(self.device) if stream is None else stream
         B.pg_run(self.ctx, self.ptrs, self.q.data_ptr(), self.ws.data_ptr(), s.cuda_stream, rounds)

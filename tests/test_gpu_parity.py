@@ -206,6 +206,92 @@ def test_sgd_step_vgg16_full_size_sampled_layers():
     gb.close()
 
 
+# ------------------------------------------------------------------ Algorithm 2, one iteration at a time
+def _check_iterate(wl, schedule, tol, eta=None):
+    """pg_iterate against the oracle's literal Algorithm 2 over a schedule of iteration counts."""
+    from oracle import pg_oracle as O
+    from parity_util import oracle_problem
+    print(f"case iterate {wl.name} schedule={schedule} eta={eta}", flush=True)
+    gb = _gb(wl)
+    gb.alloc_pstate()
+    if eta is not None:
+        gb.alloc_grads()
+    L, E = len(wl.shapes), wl.n_edges
+    X, Vq = wl.all_params(), wl.all_q()
+    Vp = [[np.zeros((wl.layer_rank(l), wl.shapes[l][0]), np.float32) for l in range(L)] for _ in range(E)]
+    prob = oracle_problem(wl)
+    rng = np.random.default_rng(17)
+    k = 0
+    for its in schedule:
+        G = None
+        if eta is not None:
+            G = [[rng.standard_normal(s).astype(np.float32) for s in wl.shapes] for _ in range(wl.n_workers)]
+            for i in range(wl.n_workers):
+                for l in range(L):
+                    gb.set_grad_layer(i, l, G[i][l])
+        gb.iterate(k, its, eta)
+        O.alg2_round(prob, X, Vq, Vp, k, its, G=G, eta=0.0 if eta is None else float(np.float32(eta)))
+        k += its
+    worst = compare_state(gb, X, Vq, list(range(L)), tol, what="iterate " + wl.name)
+    for l in range(L):
+        for e in range(E):
+            err = rel_err(gb.get_p(e, l), Vp[e][l])
+            worst["ph"] = max(worst["ph"], err)
+            assert err <= tol, f"p-state edge {e} layer {l}: {err:.3e}"
+    print("   worst rel err", worst, flush=True)
+    gb.close()
+
+
+@pytest.mark.parametrize("rank", [1, 2, 4])
+def test_single_iterations_ragged_ring(rank):
+    wl = _custom(f"iter_ragged_r{rank}", 5, W.ring_edges(5), 1 / 3, SHAPES_RAGGED, rank, 1)
+    _check_iterate(wl, [1], TOL_1)
+    _check_iterate(wl, [1, 1, 1, 1], TOL_10)
+    _check_iterate(wl, [2, 3, 1, 2], TOL_10)
+
+
+def test_single_iterations_with_gradients_on_a_torus():
+    wl = _custom("iter_torus", 9, W.torus_edges(3, 3), 1 / 5, [(120, 260), (33, 12), (40, 1)], 2, 1)
+    _check_iterate(wl, [1, 1, 2], TOL_10, eta=0.05)
+
+
+def test_two_iterations_match_one_power_step_on_the_gpu():
+    """The paper's 'PowerGossip (2 iterations)' = one pg_round power step (same approximation)."""
+    wl = W.get("resnet20")
+    a, b = _gb(wl), _gb(wl)
+    b.alloc_pstate()
+    a.round()
+    b.iterate(0, 2)
+    for i in range(wl.n_workers):
+        for l in range(len(wl.shapes)):
+            assert rel_err(b.get_layer(i, l), a.get_layer(i, l)) <= TOL_1
+    for e in range(wl.n_edges):
+        for l in range(len(wl.shapes)):
+            assert rel_err(b.get_q(e, l), a.get_q(e, l)) <= TOL_1
+    a.close(); b.close()
+
+
+def test_single_iteration_vgg16_full_size_sampled_layers():
+    wl = W.get("vgg16_r1")
+    from oracle import pg_oracle as O
+    layers = [0, 5, 13]
+    gb = _gb(wl, layers)
+    gb.alloc_pstate()
+    X, Vq = wl.all_params(layers), wl.all_q(layers)
+    Vp = [[np.zeros((1, wl.shapes[l][0]), np.float32) for l in layers] for _ in range(wl.n_edges)]
+    sub = O.Problem(wl.n_workers, wl.edges, wl.edge_w.astype(np.float64), [wl.shapes[l] for l in layers], 1, 1)
+    k = 0
+    for its in (1, 1, 1):
+        gb.iterate(k, its)
+        O.alg2_round(sub, X, Vq, Vp, k, its)
+        k += its
+    compare_state(gb, X, Vq, layers, TOL_10, what="iterate vgg16")
+    for j, l in enumerate(layers):
+        for e in range(wl.n_edges):
+            assert rel_err(gb.get_p(e, l), Vp[e][j]) <= TOL_10
+    gb.close()
+
+
 # ------------------------------------------------------------------ degenerate cases
 def test_identical_workers_are_a_fixed_point():
     from paper_2008_01425_amd.device import GossipBuffers

@@ -588,6 +588,6 @@ def test_iterated_single_steps_reach_the_top_singular_pair():
         O.alg2_round(prob, X, Vq, Vp, k, 1)
     Us, ss, Vts = np.linalg.svd(D)
     s1 = np.sign(Vp[0][0][0] @ Us[:, 0])
-    assert np.allclose(Vp[0][0][0], s1 * ss[0] * Us[:, 0], atol=1e-8) or \
-        np.allclose(np.linalg.norm(Vp[0][0][0]), ss[0], atol=1e-8)
-    assert abs(np.linalg.norm(Vq[0][0][0]) - ss[0]) < 1e-8
+    assert np.allclose(Vp[0][0][0], s1 * ss[0] * Us[:, 0], atol=1e-8)
+    s2 = np.sign(Vq[0][0][0] @ Vts[0])
+    assert np.allclose(Vq[0][0][0], s2 * ss[0] * Vts[0], atol=1e-8)

@@ -393,3 +393,17 @@ def test_resnet50_full_size_sampled_layers():
     for shape in ((64, 147), (256, 2304), (1000, 2048), (2048, 1)):
         picks.append(next(l for l in big if wl.shapes[l] == shape))
     _check(wl, 2, TOL_10, fused=True, layers=picks)
+
+
+def test_consensus_experiment_on_unstructured_data():
+    """Section 5, Figure 1 (left): on 100 x 100 Gaussian data every variant contracts towards the
+    mean round after round, and no compressed variant beats uncompressed gossip per round."""
+    from paper_2008_01425_amd.consensus_experiment import run
+    res = run(rounds=60, every=20)
+    for name, curve in res.items():
+        errs = [e for _, _, e in curve]
+        assert all(b < a for a, b in zip(errs, errs[1:])), name
+    full = res["uncompressed"][-1][2]
+    for name in ("power_iteration", "random_projection", "one_iteration"):
+        assert res[name][-1][2] >= full
+        assert res[name][-1][2] < 0.9 * res[name][0][2]

@@ -41,8 +41,9 @@ __device__ __forceinline__ float ldg1(const float *p) { return *(const PG_GLOBAL
 template <int CTRL>
 __device__ __forceinline__ double dpp_mov(double v) {
     int lo = __double2loint(v), hi = __double2hiint(v);
-    lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, false);
-    hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, false);
+    // every lane has a valid source lane under these controls, so no `old` value is needed
+    lo = __builtin_amdgcn_mov_dpp(lo, CTRL, 0xf, 0xf, false);
+    hi = __builtin_amdgcn_mov_dpp(hi, CTRL, 0xf, 0xf, false);
     return __hiloint2double(hi, lo);
 }
 __device__ __forceinline__ double swizzle_xor16(double v) {
@@ -369,6 +370,8 @@ __device__ __forceinline__ void row_wide_body(const RowTile &t, const PairDesc &
 #pragma unroll
                         for (int m = 0; m < M; ++m) xd[m][v] = fma(-cp[m][j], qd, xd[m][v]);
                     }
+                    // keep the compiler from hoisting all RC slices (and their conversions) at once
+                    if ((j & 3) == 3) PG_FENCE();
                 }
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
@@ -391,6 +394,7 @@ __device__ __forceinline__ void row_wide_body(const RowTile &t, const PairDesc &
 #pragma unroll
                         for (int m = 0; m < M; ++m) acc[m][j] = fma(xd[m][v], qd, acc[m][j]);
                     }
+                    if ((j & 3) == 3) PG_FENCE();
                 }
             }
         };

@@ -157,10 +157,14 @@ struct Launcher {
                 tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
         } else {
             // register budget: RC accumulators and RC update coefficients per row
-            constexpr int M = ((UPD && SWP) || GRAD) ? 2 : 4;
+            constexpr int M = ((UPD && SWP) || GRAD || (RC > 8 && UPD)) ? 2 : 4;
             size_t lds = (size_t)RC * rc.max_seg * sizeof(float);
-            row_wide_kernel<RC, M, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>(
-                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
+#define PG_WIDE(VV) row_wide_kernel<VV, RC, M, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>( \
+                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta)
+            if (rc.V == 4) PG_WIDE(4);
+            else if (rc.V == 2) PG_WIDE(2);
+            else PG_WIDE(1);
+#undef PG_WIDE
         }
     }
     template <int RC>
@@ -221,9 +225,17 @@ struct Launcher {
         // LDS: the staged Phat slice plus one zero row, later reused for the cross-wavefront sums
         size_t lds = std::max((size_t)(cc.max_rows + 1) * RC * sizeof(float),
                               (size_t)(kThreads / 64 - 1) * 64 * 4 * sizeof(double));
-        col_kernel<RC, U><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>(
-            c->d_col_tiles + cc.dev_first, n, /*reverse=*/c->col_reverse, c->d_pairs, c->d_cols,
-            c->d_xs, left(), qw());
+#define PG_COL(VV) col_kernel<VV, RC, U><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>( \
+            c->d_col_tiles + cc.dev_first, n, /*reverse=*/c->col_reverse, c->d_pairs, c->d_cols, \
+            c->d_xs, left(), qw())
+        if constexpr (RC < kWideCols) {
+            PG_COL(0);
+        } else {
+            if (cc.V == 4) PG_COL(4);
+            else if (cc.V == 2) PG_COL(2);
+            else PG_COL(1);
+        }
+#undef PG_COL
     }
     // The Q-sweep walks the parameters back to front: it starts on what the pass before it
     // (always a front-to-back row pass) touched last.

@@ -435,7 +435,9 @@ __device__ __forceinline__ void row_wide_body(const RowTile &t, const PairDesc &
     }
 }
 
-template <int RC, int M, bool UPDATE, bool SWEEP, bool GRAD>
+// One instantiation per vector width V: with 8-16 stacked columns a kernel that carried all
+// three widths would be allocated the registers of its widest body and lose occupancy.
+template <int V, int RC, int M, bool UPDATE, bool SWEEP, bool GRAD>
 __global__ void __launch_bounds__(kThreads)
 row_wide_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
                 const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
@@ -448,9 +450,7 @@ row_wide_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
     const PairDesc pd = pairs[t.pair];
     float *X = xs[pd.worker] + pd.x_off;
     const float *Gp = GRAD ? gs[pd.worker] + pd.x_off : nullptr;
-    if (pd.V == 4) row_wide_body<4, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, sQ, Gp, eta);
-    else if (pd.V == 2) row_wide_body<2, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, sQ, Gp, eta);
-    else row_wide_body<1, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, sQ, Gp, eta);
+    row_wide_body<V, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, sQ, Gp, eta);
 }
 
 // Workers without any edge receive no gossip term; with a gradient their step is plain SGD,
@@ -586,7 +586,8 @@ __device__ __forceinline__ void col_body(const ColTile &t, const PairDesc &pd,
     }
 }
 
-template <int RC, int U>
+// V = 0: tiles of any vector width (few stacked columns); V = 1, 2, 4: one width only.
+template <int V, int RC, int U>
 __global__ void __launch_bounds__(kThreads)
 col_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
            const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
@@ -597,9 +598,13 @@ col_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
     const ColTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
     const PairDesc pd = pairs[t.pair];
     const float *X = xs[pd.worker] + pd.x_off;
-    if (pd.V == 4) col_body<4, RC, U>(t, pd, cols, X, phat, qw, sT);
-    else if (pd.V == 2) col_body<2, RC, U>(t, pd, cols, X, phat, qw, sT);
-    else col_body<1, RC, U>(t, pd, cols, X, phat, qw, sT);
+    if constexpr (V != 0) {
+        col_body<V, RC, U>(t, pd, cols, X, phat, qw, sT);
+    } else {
+        if (pd.V == 4) col_body<4, RC, U>(t, pd, cols, X, phat, qw, sT);
+        else if (pd.V == 2) col_body<2, RC, U>(t, pd, cols, X, phat, qw, sT);
+        else col_body<1, RC, U>(t, pd, cols, X, phat, qw, sT);
+    }
 }
 
 // ---------------------------------------------------------------------------------------

@@ -302,16 +302,19 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     P.col_classes.clear();
     P.isolated_pairs.clear();
     P.isolated_elems = 0;
-    auto row_class = [&](int RC) -> size_t {
+    // many stacked columns: one class (one kernel instantiation) per vector width
+    auto row_class = [&](int RC, int V) -> size_t {
+        if (RC < kWideCols) V = 0;
         for (size_t k = 0; k < P.row_classes.size(); ++k)
-            if (P.row_classes[k].RC == RC) return k;
-        P.row_classes.push_back({RC, {}, 0, 0, 0});
+            if (P.row_classes[k].RC == RC && P.row_classes[k].V == V) return k;
+        P.row_classes.push_back({RC, V, {}, 0, 0, 0});
         return P.row_classes.size() - 1;
     };
-    auto col_class = [&](int RC) -> size_t {
+    auto col_class = [&](int RC, int V) -> size_t {
+        if (RC < kWideCols) V = 0;
         for (size_t k = 0; k < P.col_classes.size(); ++k)
-            if (P.col_classes[k].RC == RC) return k;
-        P.col_classes.push_back({RC, {}, 0, 0, 0});
+            if (P.col_classes[k].RC == RC && P.col_classes[k].V == V) return k;
+        P.col_classes.push_back({RC, V, {}, 0, 0, 0});
         return P.col_classes.size() - 1;
     };
     for (int l = 0; l < n_layers; ++l) {
@@ -326,7 +329,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
                 continue;
             }
             int RC = compiled_cols(pd.R);
-            RowClass &rc = P.row_classes[row_class(RC)];
+            RowClass &rc = P.row_classes[row_class(RC, L.V)];
             int rows_iter = g.rows_iter_base * rows_unroll(RC);
             int tile_rows;
             if (RC < kWideCols) {
@@ -348,7 +351,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
                     rc.tiles.push_back({pair, r0, std::min(tile_rows, L.p - r0), sg});
             rc.elems += (double)L.p * L.q;
 
-            ColClass &cc = P.col_classes[col_class(RC)];
+            ColClass &cc = P.col_classes[col_class(RC, L.V)];
             int cw = g.lg * L.V;
             for (int b = 0; b < g.nblk; ++b)
                 for (int c0 = 0; c0 < L.q; c0 += cw) cc.tiles.push_back({pair, c0, b, 0});

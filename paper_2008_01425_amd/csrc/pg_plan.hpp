@@ -19,6 +19,7 @@ struct LayerInfo {
 // layer, worker, rows: the address order every pass walks (forwards or backwards).
 struct RowClass {
     int RC;
+    int V;                  // 0: any vector width (RC < kWideCols); else the one width of this class
     std::vector<RowTile> tiles;
     size_t dev_first = 0;   // index of the first tile in the uploaded table
     double elems = 0;       // parameter elements covered (for byte accounting)
@@ -26,6 +27,7 @@ struct RowClass {
 };
 struct ColClass {
     int RC;
+    int V;                  // as in RowClass
     std::vector<ColTile> tiles;
     size_t dev_first = 0;
     double elems = 0;

@@ -28,10 +28,29 @@ class pg_kernel_time(ctypes.Structure):
                 ("ms", ctypes.c_double), ("bytes", ctypes.c_double)]
 
 
+def _share_hip_runtime_with_torch():
+    """One HIP runtime per process.  PyTorch wheels bundle their own libamdhip64 (same soname
+    as the system copy this library is linked against).  Loaded after torch, the library binds
+    to the copy torch already mapped; loaded first, it would map the system copy, torch would
+    later map its own, and whichever runtime initialises second finds no device.  Mapping
+    torch's copy first (without importing torch) makes the order irrelevant."""
+    import importlib.util
+    try:
+        spec = importlib.util.find_spec("torch")
+    except (ImportError, ValueError):
+        spec = None
+    if spec is None or not spec.submodule_search_locations:
+        return
+    bundled = os.path.join(list(spec.submodule_search_locations)[0], "lib", "libamdhip64.so")
+    if os.path.exists(bundled):
+        ctypes.CDLL(bundled, mode=ctypes.RTLD_GLOBAL)
+
+
 def _load():
     if not os.path.exists(LIB_PATH):
         from . import build as _build
         _build.build(force=True)
+    _share_hip_runtime_with_torch()
     lib = ctypes.CDLL(LIB_PATH)
     vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.pg_strerror.restype = ctypes.c_char_p

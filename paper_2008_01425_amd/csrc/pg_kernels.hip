@@ -99,14 +99,14 @@ __device__ __forceinline__ void group_sum_all(double (&v)[N], int width) {
 // Row-owner kernel for few stacked columns (RC <= 4): one wavefront per tile.  A group of `lpr`
 // lanes walks along M rows of X_i at once with vector loads; per column step it holds the RC
 // stacked right-hand-side columns for its slice in registers (they come from L1/L2).  The
-// loads of step c + 1 are issued before the arithmetic of step c.
+// loads of step c + D are issued before the arithmetic of step c.
 //   SWEEP : Pw[j][row] = sum_c X[row, c] * Q_j[c]            (Algorithm 2, odd iteration:
 //           p_i = X_i v for every incident edge's v in one read of X_i)
 //   UPDATE: X[row, c] -= sum_j coef_j * Phat_j[row] * Q'_j[c] (Eq. (2) summed over the edges)
 //   both  : the update, then the next round's sweep on the updated values -- the next
 //           round's right-hand side is exactly the Q' just applied (warm start).
 // ---------------------------------------------------------------------------------------
-template <int V, int RC, int M, bool UPDATE, bool SWEEP, bool GRAD>
+template <int V, int RC, int M, int D, bool UPDATE, bool SWEEP, bool GRAD>
 __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
                                          const ColDesc *__restrict__ cols, float *X,
                                          const float *__restrict__ qstate,
@@ -203,31 +203,37 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
             }
         };
 
-        int c = c_begin + sub * V;
-        if (c < c_end) {
-            vec xa[M], qa[RC], xb[M], qb[RC], ga[GRAD ? M : 1], gb[GRAD ? M : 1];
-            int rem = (c_end - c - 1) / step;  // steps after the first one
-            // PG_FENCE keeps the compiler from sinking a prefetch below the arithmetic it overlaps
-            load(c, xa, qa, ga);
-            while (rem >= 2) {
-                load(c + step, xb, qb, gb);
-                PG_FENCE();
-                process(c, xa, qa, ga);
-                PG_FENCE();
-                load(c + 2 * step, xa, qa, ga);
-                PG_FENCE();
-                process(c + step, xb, qb, gb);
-                PG_FENCE();
-                c += 2 * step;
-                rem -= 2;
+        const int c0 = c_begin + sub * V;
+        if (c0 < c_end) {
+            // Software pipeline over the column steps: the loads of step s + D are issued before
+            // the arithmetic of step s, through a ring of D + 1 register buffers (indices are
+            // compile-time after unrolling).  PG_FENCE keeps the compiler from sinking a prefetch
+            // below the arithmetic it overlaps.
+            constexpr int NB = D + 1;
+            vec xb[NB][M], qb[NB][RC], gb[NB][GRAD ? M : 1];
+            const int nsteps = (c_end - c0 - 1) / step + 1;
+#pragma unroll
+            for (int k = 0; k < D; ++k)
+                if (k < nsteps) load(c0 + k * step, xb[k], qb[k], gb[k]);
+            int s = 0;
+            for (; s + NB + D <= nsteps; s += NB) {
+#pragma unroll
+                for (int k = 0; k < NB; ++k) {
+                    load(c0 + (s + k + D) * step, xb[(k + D) % NB], qb[(k + D) % NB], gb[(k + D) % NB]);
+                    PG_FENCE();
+                    process(c0 + (s + k) * step, xb[k], qb[k], gb[k]);
+                    PG_FENCE();
+                }
             }
-            if (rem == 1) {
-                load(c + step, xb, qb, gb);
-                PG_FENCE();
-                process(c, xa, qa, ga);
-                process(c + step, xb, qb, gb);
-            } else {
-                process(c, xa, qa, ga);
+#pragma unroll
+            for (int k = 0; k < NB + D - 1; ++k) {
+                if (s + k < nsteps) {
+                    if (s + k + D < nsteps)
+                        load(c0 + (s + k + D) * step, xb[(k + D) % NB], qb[(k + D) % NB], gb[(k + D) % NB]);
+                    PG_FENCE();
+                    process(c0 + (s + k) * step, xb[k % NB], qb[k % NB], gb[k % NB]);
+                    PG_FENCE();
+                }
             }
         }
         if (SWEEP) {
@@ -248,7 +254,7 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
 // One wavefront per tile; `reverse` walks the tile list backwards so that a pass can start on
 // the data the previous pass touched last (still resident in the memory-side cache).
 //   GRAD  : (with UPDATE) also subtract eta * G[row, c]: line 6 of Algorithm 1 in one pass.
-template <int RC, int M, bool UPDATE, bool SWEEP, bool GRAD>
+template <int RC, int M, int D, bool UPDATE, bool SWEEP, bool GRAD>
 __global__ void __launch_bounds__(kRowThreads)
 row_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
            const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
@@ -259,9 +265,9 @@ row_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
     const PairDesc pd = pairs[t.pair];
     float *X = xs[pd.worker] + pd.x_off;
     const float *Gp = GRAD ? gs[pd.worker] + pd.x_off : nullptr;
-    if (pd.V == 4) row_body<4, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
-    else if (pd.V == 2) row_body<2, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
-    else row_body<1, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
+    if (pd.V == 4) row_body<4, RC, M, D, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
+    else if (pd.V == 2) row_body<2, RC, M, D, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
+    else row_body<1, RC, M, D, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
 }
 
 // ---------------------------------------------------------------------------------------

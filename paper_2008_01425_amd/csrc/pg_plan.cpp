@@ -23,7 +23,7 @@ int compiled_cols(int R) {
 }
 
 int rows_unroll(int RC) {
-    if (RC <= 2) return 8;
+    if (RC < kWideCols) return 8;
     return 4;
 }
 

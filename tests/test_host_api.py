@@ -155,3 +155,19 @@ def test_seeded_blocks_are_reproducible_and_independent():
     assert abs(d.std() - 0.1) < 0.01
     q = wl.q_init(1, 0)
     assert q.shape == (1, 32) and abs(q.std() - 1.0) < 0.3
+
+
+def test_one_hip_runtime_whichever_of_library_and_torch_loads_first():
+    """The library must share torch's HIP runtime also when it is loaded before torch (host-only
+    tests collected ahead of GPU tests do exactly that); two runtimes in one process leave the
+    second without a device."""
+    import subprocess
+    import sys
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "from paper_2008_01425_amd import binding\n"
+            "import torch\n"
+            "paths = {l.split()[-1] for l in open('/proc/self/maps') if 'libamdhip64' in l}\n"
+            "print(len(paths))\n" % ROOT)
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr[-2000:]
+    assert out.stdout.strip().splitlines()[-1] == "1"

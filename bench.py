@@ -188,6 +188,22 @@ def main():
     gb.close()
     del gb
     torch.cuda.empty_cache()
+    # ---- practical ceiling: a plain device-to-device copy of 1 GiB (read + write counted) ----
+    n_copy = (1 << 30) // 4
+    src = torch.ones(n_copy, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(20):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    dt_copy = (time.perf_counter() - t0) / 20
+    result["copy_ceiling"] = {"GBps": 8.0 * n_copy / dt_copy / 1e9, "frac_of_peak": 8.0 * n_copy / dt_copy / 1e9 / HBM_PEAK_GBS,
+                              "what": "torch device-to-device copy of 1 GiB, bytes read + bytes written per second"}
+    del src, dst
+    torch.cuda.empty_cache()
     if args.copy_calibration > 0:
         n = args.copy_calibration * (1 << 20) // 4
         src = torch.ones(n, dtype=torch.float32, device="cuda")

@@ -106,6 +106,13 @@ int do_upload(pg_ctx *c) {
 // part of the M * RC accumulators and update coefficients then lives in accumulation registers.
 constexpr int kRowsPerGroup = 8;
 constexpr int kPrefetchSteps = 1;
+// Matrix-core kernels: steps a row tile and a column tile load ahead.
+#ifndef PG_MCFG
+#define PG_MCFG 2, 2
+#endif
+constexpr int kMfmaCfg[2] = {PG_MCFG};
+constexpr int kMfmaRowPrefetch = kMfmaCfg[0];
+constexpr int kMfmaColPrefetch = kMfmaCfg[1];
 
 struct Launcher {
     pg_ctx *c;
@@ -162,6 +169,14 @@ struct Launcher {
         if constexpr (RC < kWideCols) {
             row_kernel<RC, kRowsPerGroup, kPrefetchSteps, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
                 tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
+        } else if (c->plan.mfma_rows) {
+#define PG_MROW(VV) mrow_kernel<VV, RC / 4, kMfmaRowBlocks, kMfmaRowPrefetch, UPD, SWP, GRAD> \
+                <<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>( \
+                tiles, n, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta)
+            if (rc.V == 4) PG_MROW(4);
+            else if (rc.V == 2) PG_MROW(2);
+            else PG_MROW(1);
+#undef PG_MROW
         } else {
             // register budget: RC accumulators and RC update coefficients per row
             constexpr int M = ((UPD && SWP) || GRAD || (RC > 8 && UPD)) ? 2 : 4;
@@ -179,7 +194,7 @@ struct Launcher {
         if (grad) {
             row_launch<RC, true, false, true>(rc);
         } else if (upd && swp) {
-            if constexpr (RC <= kWideCols) {
+            if (RC <= kWideCols || c->plan.mfma_rows) {
                 row_launch<RC, true, true>(rc);
             } else {
                 // with many stacked columns the fused pass does not fit in registers and is bound
@@ -237,6 +252,14 @@ struct Launcher {
             c->d_xs, left(), qw())
         if constexpr (RC < kWideCols) {
             PG_COL(0);
+        } else if (c->plan.mfma_cols) {
+#define PG_MCOL(VV) mcol_kernel<VV, kMfmaColPrefetch><<<dim3((unsigned)n), dim3(kThreads), 0, st>>>( \
+            c->d_col_tiles + cc.dev_first, n, /*reverse=*/c->col_reverse, c->d_pairs, c->d_cols, \
+            c->d_xs, left(), qw())
+            if (cc.V == 4) PG_MCOL(4);
+            else if (cc.V == 2) PG_MCOL(2);
+            else PG_MCOL(1);
+#undef PG_MCOL
         } else {
             if (cc.V == 4) PG_COL(4);
             else if (cc.V == 2) PG_COL(2);
@@ -407,6 +430,9 @@ int pg_init(pg_ctx **out, int n_workers, int n_edges, const int32_t *edges, cons
     if (const char *e = getenv("PG_ROW_TILE_BYTES")) tune.row_tile_bytes = std::max(1024, atoi(e));
     if (const char *e = getenv("PG_COL_REVERSE")) c->col_reverse = atoi(e) != 0;
     if (const char *e = getenv("PG_COL_TILE_BYTES")) tune.col_tile_bytes = std::max(1024, atoi(e));
+    if (const char *e = getenv("PG_WIDE_TILE_BYTES")) tune.wide_tile_bytes = std::max(1024, atoi(e));
+    if (const char *e = getenv("PG_MFMA_ROWS")) tune.mfma_rows = atoi(e) != 0;
+    if (const char *e = getenv("PG_MFMA_COLS")) tune.mfma_cols = atoi(e) != 0;
     int rc;
     try {
         rc = build_plan(c->plan, n_workers, n_edges, edges, edge_w, n_layers, rows, cols, rank,

@@ -14,6 +14,8 @@ constexpr int kThreads = 256;  // work-group size of the column-owner and combin
 constexpr int kRowThreads = 64;  // narrow row-owner kernels: one wavefront per tile
 constexpr int kWideCols = 8;     // from this many compiled columns on, row tiles stage Q in LDS
 constexpr int kWideLdsBytes = 48 * 1024;  // LDS budget of a wide row tile's Q slice
+constexpr int kMfmaRowBlocks = 4;  // matrix-core row tiles: blocks of 16 rows per wavefront
+constexpr int kMfmaTileCols = 256;  // matrix-core column tiles: columns per tile (four wavefronts)
 
 // One stacked column of a (worker, layer) pair.
 struct ColDesc {

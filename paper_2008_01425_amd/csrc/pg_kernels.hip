@@ -459,6 +459,347 @@ row_wide_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
     row_wide_body<V, RC, M, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, sQ, Gp, eta);
 }
 
+// ---------------------------------------------------------------------------------------
+// Matrix-core kernels for many stacked columns (8 or 16).  With 16 right-hand sides a pass is a
+// p x q by q x 16 contraction: on the vector ALUs its 16 double multiply-adds per loaded float
+// (plus operand conversions and lane reductions) take longer than the HBM read.  The double
+// precision matrix instruction V_MFMA_F64_16X16X4_F64 does the same 1024 multiply-adds in one
+// issue slot, sums over lanes inside the instruction and keeps a 16 x 16 accumulator in eight
+// registers, which leaves the vector ALUs to the float -> double conversions and the memory
+// pipeline to the loads.  Lane layout of D = A B + C (lo = lane % 16, hi = lane / 16):
+//   A[i][k]: lane (lo = i, hi = k);   B[k][j]: lane (hi = k, lo = j);
+//   D[i][j]: lane (lo = j, hi = i % 4), register i / 4.
+// ---------------------------------------------------------------------------------------
+typedef double mfma_acc __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ mfma_acc mfma16(double a, double b, mfma_acc c) {
+    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
+// Four consecutive floats of a row as 4 / V vector loads.  `nvalid` (a multiple of V) floats
+// from p on are inside the row; units past them re-read the last valid unit and come back as
+// zeros.  nvalid >= 4 is the plain case.
+// Four consecutive floats in one 16-byte load at any 4-byte aligned address (global memory
+// takes under-aligned vector accesses; rows of a matrix with q % 4 != 0 start at such addresses).
+typedef float float4_any __attribute__((ext_vector_type(4), aligned(4)));
+__device__ __forceinline__ void ld4(const float *p, float (&x)[4]) {
+    const float4_any t = *(const PG_GLOBAL float4_any *)p;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) x[v] = t[v];
+}
+template <int V>
+__device__ __forceinline__ void ld4(const float *p, float (&x)[4]) {
+#pragma unroll
+    for (int u = 0; u < 4 / V; ++u) {
+        const typename VecT<V>::T t = ldg<V>(p + V * u);
+#pragma unroll
+        for (int v = 0; v < V; ++v) x[V * u + v] = t[v];
+    }
+}
+template <int V>
+__device__ __forceinline__ void ld4_edge(const float *p, int nvalid, float (&x)[4]) {
+#pragma unroll
+    for (int u = 0; u < 4 / V; ++u) {
+        const bool ok = V * u < nvalid;
+        const typename VecT<V>::T t = ldg<V>(p + (ok ? V * u : nvalid - V));
+#pragma unroll
+        for (int v = 0; v < V; ++v) x[V * u + v] = ok ? t[v] : 0.0f;
+    }
+}
+template <int V>
+__device__ __forceinline__ void st4_edge(float *p, int nvalid, const float (&x)[4]) {
+#pragma unroll
+    for (int u = 0; u < 4 / V; ++u) {
+        typename VecT<V>::T t;
+#pragma unroll
+        for (int v = 0; v < V; ++v) t[v] = x[V * u + v];
+        if (V * u < nvalid) stg<V>(p + V * u, t);
+    }
+}
+
+// Row-owner pass on the matrix cores: one wavefront per tile of MB blocks of 16 rows by one
+// column segment, 16 columns per step.  Lane (lo, hi) holds X[row lo of the block][c + 4 hi + v],
+// v = 0..3.
+//   SWEEP : D[row][j] += X[row][c + 4 hi + v] * Q_j[c + 4 hi + v], one instruction per v
+//           (A = X, B = the stacked right-hand sides, j = lo);
+//   UPDATE: transposed, so that the result lands in the layout the values were loaded in:
+//           D[col][row] = X[row][col] - sum_j Q'_j[col] * (coef_j Phat_j[row]), four stacked
+//           columns j = 4 m + hi per instruction (A = -Q', B = coef * Phat, C = X);
+//   both  : the sweep multiplies the stored (rounded) values.
+// RCM = compiled stacked columns / 4 (2 or 4): the instructions one update block takes.
+template <int V, int RCM, int MB, int D, bool UPDATE, bool SWEEP, bool GRAD>
+__global__ void __launch_bounds__(kRowThreads)
+mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, const PairDesc *__restrict__ pairs,
+            const ColDesc *__restrict__ cols, float *const *__restrict__ xs,
+            const float *__restrict__ qstate, const float *__restrict__ phat,
+            double *__restrict__ pw, const float *const *__restrict__ gs, double eta) {
+    const RowTile t = tiles[blockIdx.x];
+    const PairDesc pd = pairs[t.pair];
+    float *X = xs[pd.worker] + pd.x_off;
+    const float *Gp = GRAD ? gs[pd.worker] + pd.x_off : nullptr;
+    const int lane = threadIdx.x, lo = lane & 15, hi = lane >> 4;
+    const int q = pd.q, R = pd.R;
+    const int c_begin = t.seg * pd.seg_len;
+    const int c_end = min(q, c_begin + pd.seg_len);
+    const int nsteps = (c_end - c_begin + 15) >> 4;
+    const bool ragged = ((c_end - c_begin) & 15) != 0;
+    const int row_end = t.row0 + t.nrows;
+    const int nrb = (t.nrows + 15) >> 4;  // blocks of 16 rows in this tile, at most MB
+
+    bool rok[MB];
+    int64_t roff[MB];  // float offset of this lane's first element at column 0 of the segment
+    int rowi[MB];
+#pragma unroll
+    for (int b = 0; b < MB; ++b) {
+        const int r = t.row0 + 16 * b + lo;
+        rok[b] = r < row_end;
+        rowi[b] = rok[b] ? r : row_end - 1;
+        roff[b] = (int64_t)rowi[b] * q + 4 * hi;
+    }
+    // sweep operand B: stacked column lo at columns c + 4 hi + v
+    const float *qs = qstate + cols[pd.col0 + min(lo, R - 1)].q_off + 4 * hi;
+    // update operands: A = -Q'_j at column c + 4 (lo % 4) + lo / 4 (the column D's row index lo
+    // stands for), B = coef_j * Phat_j[row lo], both for j = 4 m + hi
+    const float *qu[RCM];
+    double cp[MB][RCM];
+    if (UPDATE) {
+#pragma unroll
+        for (int m = 0; m < RCM; ++m) {
+            const int j = 4 * m + hi;
+            const ColDesc cd = cols[pd.col0 + min(j, R - 1)];
+            qu[m] = qstate + cd.q_off + 4 * (lo & 3) + (lo >> 2);
+            const double coef = (j < R) ? (double)cd.coef : 0.0;
+#pragma unroll
+            for (int b = 0; b < MB; ++b) cp[b][m] = coef * (double)ldg1(phat + cd.ph_off + rowi[b]);
+        }
+    }
+    mfma_acc acc[MB];
+#pragma unroll
+    for (int b = 0; b < MB; ++b) acc[b] = mfma_acc{0.0, 0.0, 0.0, 0.0};
+
+    struct Buf {
+        float x[MB][4];
+        float g[GRAD ? MB : 1][4];
+        float qs[4];
+        float qu[RCM];
+    };
+    auto load = [&](int s, Buf &f) {
+        const int c = c_begin + 16 * s;
+        const bool edge = ragged && s == nsteps - 1;
+        const int nvalid = c_end - (c + 4 * hi);  // this lane's valid floats (may be <= 0 on the edge)
+        if (!edge) {
+            if (SWEEP) ld4<V>(qs + c, f.qs);
+#pragma unroll
+            for (int b = 0; b < MB; ++b)
+                if (b < nrb) ld4<V>(X + roff[b] + c, f.x[b]);
+            if (GRAD) {
+#pragma unroll
+                for (int b = 0; b < MB; ++b)
+                    if (b < nrb) ld4<V>(Gp + roff[b] + c, f.g[GRAD ? b : 0]);
+            }
+        } else {
+            if (SWEEP) ld4_edge<V>(qs + c, nvalid, f.qs);
+#pragma unroll
+            for (int b = 0; b < MB; ++b)
+                if (b < nrb) ld4_edge<V>(X + roff[b] + c, nvalid, f.x[b]);
+            if (GRAD) {
+#pragma unroll
+                for (int b = 0; b < MB; ++b)
+                    if (b < nrb) ld4_edge<V>(Gp + roff[b] + c, nvalid, f.g[GRAD ? b : 0]);
+            }
+        }
+        if (UPDATE) {
+            // past the right edge any column inside the segment will do: those results are not stored
+            const int cu = edge ? min(0, c_end - 1 - (c + 4 * (lo & 3) + (lo >> 2))) : 0;
+#pragma unroll
+            for (int m = 0; m < RCM; ++m) f.qu[m] = ldg1(qu[m] + c + cu);
+        }
+    };
+    auto process = [&](int s, Buf &f) {
+        const int c = c_begin + 16 * s;
+        const bool edge = ragged && s == nsteps - 1;
+        const int nvalid = edge ? c_end - (c + 4 * hi) : 4;
+        double qsd[4], qud[RCM];
+        if (SWEEP) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) qsd[v] = (double)f.qs[v];
+        }
+        if (UPDATE) {
+#pragma unroll
+            for (int m = 0; m < RCM; ++m) qud[m] = -(double)f.qu[m];
+        }
+#pragma unroll
+        for (int b = 0; b < MB; ++b) {
+            if (b < nrb) {
+                mfma_acc d;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    d[v] = (double)f.x[b][v];
+                    if (GRAD) d[v] = fma(-eta, (double)f.g[GRAD ? b : 0][v], d[v]);
+                }
+                if (UPDATE) {
+#pragma unroll
+                    for (int m = 0; m < RCM; ++m)
+                        if (4 * m < R) d = mfma16(qud[m], cp[b][m], d);
+                    float xn[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        xn[v] = (float)d[v];
+                        d[v] = (v < nvalid) ? (double)xn[v] : 0.0;  // the sweep uses the stored (rounded) value
+                    }
+                    if (rok[b]) st4_edge<V>(X + roff[b] + c, nvalid, xn);
+                }
+                if (SWEEP) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[b] = mfma16(d[v], qsd[v], acc[b]);
+                }
+            }
+        }
+    };
+
+    // software pipeline: loads of step s + D are issued before the arithmetic of step s
+    constexpr int NB = D + 1;
+    Buf ring[NB];
+#pragma unroll
+    for (int k = 0; k < D; ++k)
+        if (k < nsteps) load(k, ring[k]);
+    int s = 0;
+    for (; s + NB + D <= nsteps; s += NB) {
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            load(s + k + D, ring[(k + D) % NB]);
+            PG_FENCE();
+            process(s + k, ring[k]);
+            PG_FENCE();
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < NB + D - 1; ++k) {
+        if (s + k < nsteps) {
+            if (s + k + D < nsteps) load(s + k + D, ring[(k + D) % NB]);
+            PG_FENCE();
+            process(s + k, ring[k % NB]);
+            PG_FENCE();
+        }
+    }
+
+    if (SWEEP && lo < R) {
+        double *dst = pw + pd.pw_off + ((int64_t)t.seg * R + lo) * pd.p;
+#pragma unroll
+        for (int b = 0; b < MB; ++b)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const int r = t.row0 + 16 * b + 4 * w + hi;
+                if (r < row_end) dst[r] = acc[b][w];
+            }
+    }
+}
+
+// Column-owner pass (Q-sweep) on the matrix cores: four wavefronts per tile, each on its own
+// 64 adjacent columns of one row block (side by side, so that the four read the same DRAM pages
+// at about the same time; they share nothing and never wait for each other), 16 rows per step.
+// Lane (lo, hi) holds, for u = 0..3, four floats of row r + 4 hi + u, fetched as 4 / V loads of
+// V floats in which the 16 lanes lo sit side by side: float v is column c0 + V lo + v % V +
+// 16 V (v / V).  The instruction for (u, v) adds X^T Phat over the rows r + 4 hi + u, hi = 0..3:
+// D_v[col][j] += X[row][col] * Phat_j[row] (A = X^T, B = the stacked Phat columns, j = lo); a
+// lane's four Phat values of a step are consecutive in memory and come in one load.
+template <int V, int D>
+__global__ void __launch_bounds__(kThreads)
+mcol_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
+            const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
+            float *const *__restrict__ xs, const float *__restrict__ phat,
+            double *__restrict__ qw) {
+    const ColTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
+    const PairDesc pd = pairs[t.pair];
+    const float *X = xs[pd.worker] + pd.x_off;
+    const int lane = threadIdx.x & 63, lo = lane & 15, hi = lane >> 4;
+    const int q = pd.q, R = pd.R;
+    const int c0 = t.c0 + 64 * (int)(threadIdx.x >> 6);
+    if (c0 >= q) return;
+    const int ncols = min(64, q - c0);  // this wavefront's columns inside the matrix
+    const int rb = t.blk * pd.blk_rows;
+    const int re = min(pd.p, rb + pd.blk_rows);
+    const int nsteps = (re - rb + 15) >> 4;
+    const bool ragged = ((re - rb) & 15) != 0;
+    const float *ph = phat + cols[pd.col0 + min(lo, R - 1)].ph_off;
+    const bool jok = lo < R;
+    const float *xt = X + c0;
+
+    mfma_acc acc[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] = mfma_acc{0.0, 0.0, 0.0, 0.0};
+
+    struct Buf {
+        float x[4][4];
+        float t[4];
+    };
+    auto load = [&](int s, Buf &f) {
+        const int r0 = rb + 16 * s + 4 * hi;
+        const bool last = ragged && s == nsteps - 1;
+        if (!last) ld4(ph + r0, f.t);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = last ? min(r0 + u, re - 1) : r0 + u;
+            if (last) f.t[u] = ldg1(ph + r);
+            const float *xr = xt + (int64_t)r * q;
+#pragma unroll
+            for (int w = 0; w < 4 / V; ++w) {
+                const int cw = 16 * V * w + V * lo;
+                // a lane past the row's end reads the row's start: that sum is not stored
+                const typename VecT<V>::T xv = ldg<V>(xr + (cw < ncols ? cw : -c0));
+#pragma unroll
+                for (int e = 0; e < V; ++e) f.x[u][V * w + e] = xv[e];
+            }
+        }
+    };
+    auto process = [&](int s, Buf &f) {
+        const int r0 = rb + 16 * s + 4 * hi;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const double td = (jok && r0 + u < re) ? (double)f.t[u] : 0.0;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[v] = mfma16((double)f.x[u][v], td, acc[v]);
+        }
+    };
+
+    constexpr int NB = D + 1;
+    Buf ring[NB];
+#pragma unroll
+    for (int k = 0; k < D; ++k)
+        if (k < nsteps) load(k, ring[k]);
+    int s = 0;
+    for (; s + NB + D <= nsteps; s += NB) {
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            load(s + k + D, ring[(k + D) % NB]);
+            PG_FENCE();
+            process(s + k, ring[k]);
+            PG_FENCE();
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < NB + D - 1; ++k) {
+        if (s + k < nsteps) {
+            if (s + k + D < nsteps) load(s + k + D, ring[(k + D) % NB]);
+            PG_FENCE();
+            process(s + k, ring[k % NB]);
+            PG_FENCE();
+        }
+    }
+
+    // D_v[i][j] sits in lane (lo = j, hi = i % 4), register i / 4; i stands for column
+    // c0 + V i + v % V + 16 V (v / V)
+    if (jok) {
+        double *dst = qw + pd.qw_off + ((int64_t)t.blk * R + lo) * q + c0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int cc = V * (4 * w + hi) + v % V + 16 * V * (v / V);
+                if (cc < ncols) dst[cc] = acc[v][w];
+            }
+    }
+}
+
 // Workers without any edge receive no gossip term; with a gradient their step is plain SGD,
 // X -= eta * G, elementwise over the listed (worker, layer) pairs.
 __global__ void __launch_bounds__(kThreads)

@@ -38,6 +38,8 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     P.n_layers = n_layers;
     P.rank = rank;
     P.steps = power_steps;
+    P.mfma_rows = tune.mfma_rows;
+    P.mfma_cols = tune.mfma_cols;
     P.edges.assign(edges, edges + 2 * (size_t)n_edges);
     P.edge_w.assign(edge_w, edge_w + n_edges);
 
@@ -136,7 +138,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         g.wide = rc_max >= kWideCols;
         // Lanes per row: a whole wavefront for few stacked columns; 16 for many, where the
         // per-row lane reduction (RC values per row) would otherwise rival the products.
-        g.lpr = std::min(g.wide ? 16 : 64, pow2_ceil(nv));
+        g.lpr = std::min((g.wide && !tune.mfma_rows) ? 16 : 64, pow2_ceil(nv));
         int chunk = g.lpr * L.V;  // floats one lane group covers per step
         int nchunks = (L.q + chunk - 1) / chunk;
         int seg_chunks;
@@ -147,6 +149,13 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             int64_t chunk_bytes = (int64_t)rows_iter * chunk * 4;
             seg_chunks = (int)std::max<int64_t>(1, tn.row_tile_bytes / chunk_bytes);
             g.rows_iter_base = 64 / g.lpr;
+        } else if (tune.mfma_rows) {
+            // matrix cores: one wavefront per tile of 16 * kMfmaRowBlocks rows, 16 columns a step
+            chunk = 16;
+            nchunks = (L.q + chunk - 1) / chunk;
+            int64_t chunk_bytes = (int64_t)16 * kMfmaRowBlocks * chunk * 4;
+            seg_chunks = (int)std::max<int64_t>(1, tn.wide_tile_bytes / 2 / chunk_bytes);
+            g.rows_iter_base = 64 / g.lpr;  // for this layer's workers with few stacked columns
         } else {
             // four wavefronts per tile share the Q slice in LDS: RC * seg_len floats must fit
             seg_chunks = std::max(1, kWideLdsBytes / (rc_max * 4) / chunk);
@@ -179,6 +188,11 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         int64_t row_bytes = (int64_t)g.lg * L.V * 4;
         int64_t want = std::max<int64_t>(1, tn.col_tile_bytes / row_bytes);
         int64_t unit = (int64_t)row_groups * kColUnroll;
+        if (g.wide && tune.mfma_cols) {
+            // four wavefronts per tile of kMfmaTileCols columns
+            want = std::max<int64_t>(16, tn.wide_tile_bytes * 2 / (kMfmaTileCols * 4));
+            unit = 16;
+        }
         int64_t br = round_up(want, unit);
         if (br >= L.p) br = L.p;
         g.blk_rows = (int)br;
@@ -339,6 +353,8 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
                     iters = (int)std::max<int64_t>(1, tn.row_tile_bytes / bytes_iter);
                 }
                 tile_rows = rows_iter * iters;
+            } else if (tune.mfma_rows) {
+                tile_rows = 16 * kMfmaRowBlocks;
             } else {
                 // enough rows that staging the Q slice (RC rows' worth of traffic) is amortised
                 int64_t seg_bytes = (int64_t)std::min(g.seg_len, L.q) * 4;
@@ -352,7 +368,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             rc.elems += (double)L.p * L.q;
 
             ColClass &cc = P.col_classes[col_class(RC, L.V)];
-            int cw = g.lg * L.V;
+            int cw = (RC >= kWideCols && tune.mfma_cols) ? kMfmaTileCols : g.lg * L.V;
             for (int b = 0; b < g.nblk; ++b)
                 for (int c0 = 0; c0 < L.q; c0 += cw) cc.tiles.push_back({pair, c0, b, 0});
             cc.elems += (double)L.p * L.q;

@@ -38,10 +38,14 @@ struct Tuning {
     int row_tile_bytes = 72 * 1024;  // target parameter bytes per row-owner tile (one wavefront)
     int col_tile_bytes = 512 * 1024; // target parameter bytes per column-owner tile (four wavefronts)
     int wide_tile_bytes = 256 * 1024; // target parameter bytes per wide row-owner tile (four wavefronts)
+    // 8-16 stacked columns: which passes run on the matrix cores
+    bool mfma_cols = true;            // Q-sweep
+    bool mfma_rows = false;           // P-sweep and update
 };
 
 struct Plan {
     int n = 0, n_edges = 0, n_layers = 0, rank = 0, steps = 0;
+    bool mfma_rows = false, mfma_cols = true; // passes over 8-16 stacked columns that run on the matrix cores
     std::vector<int32_t> edges;   // 2 * n_edges
     std::vector<float> edge_w;
     std::vector<LayerInfo> layers;

@@ -171,3 +171,15 @@ def test_one_hip_runtime_whichever_of_library_and_torch_loads_first():
     out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
     assert out.returncode == 0, out.stderr[-2000:]
     assert out.stdout.strip().splitlines()[-1] == "1"
+
+
+def test_plan_with_mixed_degrees_in_one_layer():
+    """Workers of degree 3, 2, 1 and 0 at rank 4: one layer then holds workers with 12, 8 and 4
+    stacked columns (different kernel families share the layer's segment geometry) and one
+    without any."""
+    edges = [[0, 1], [2, 0], [0, 3], [3, 1]]
+    shapes = [(48, 36), (17, 1), (20, 64), (300, 650)]
+    ctx = _init(5, edges, [0.3, 0.2, 0.25, 0.4], shapes, rank=4, steps=2)
+    assert B.pg_message_floats(ctx) == sum(min(4, p, q) * (p + q) for p, q in shapes)
+    assert B.pg_workspace_bytes(ctx) > 0
+    B.pg_destroy(ctx)

@@ -106,13 +106,10 @@ int do_upload(pg_ctx *c) {
 // part of the M * RC accumulators and update coefficients then lives in accumulation registers.
 constexpr int kRowsPerGroup = 8;
 constexpr int kPrefetchSteps = 1;
-// Matrix-core kernels: steps a row tile and a column tile load ahead.
-#ifndef PG_MCFG
-#define PG_MCFG 2, 2
-#endif
-constexpr int kMfmaCfg[2] = {PG_MCFG};
-constexpr int kMfmaRowPrefetch = kMfmaCfg[0];
-constexpr int kMfmaColPrefetch = kMfmaCfg[1];
+// Matrix-core kernels: steps a row tile and a column tile load ahead (measured on the
+// LSTM-shaped torus: deeper rings only cost registers).
+constexpr int kMfmaRowPrefetch = 1;
+constexpr int kMfmaColPrefetch = 2;
 
 struct Launcher {
     pg_ctx *c;
@@ -169,9 +166,9 @@ struct Launcher {
         if constexpr (RC < kWideCols) {
             row_kernel<RC, kRowsPerGroup, kPrefetchSteps, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
                 tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
-        } else if (c->plan.mfma_rows) {
+        } else if (rc.mfma) {
 #define PG_MROW(VV) mrow_kernel<VV, RC / 4, kMfmaRowBlocks, kMfmaRowPrefetch, UPD, SWP, GRAD> \
-                <<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>( \
+                <<<dim3((unsigned)n), dim3(kThreads), kMrowLdsBytes, st>>>( \
                 tiles, n, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta)
             if (rc.V == 4) PG_MROW(4);
             else if (rc.V == 2) PG_MROW(2);
@@ -194,7 +191,7 @@ struct Launcher {
         if (grad) {
             row_launch<RC, true, false, true>(rc);
         } else if (upd && swp) {
-            if (RC <= kWideCols || c->plan.mfma_rows) {
+            if (RC <= kWideCols || rc.mfma) {
                 row_launch<RC, true, true>(rc);
             } else {
                 // with many stacked columns the fused pass does not fit in registers and is bound

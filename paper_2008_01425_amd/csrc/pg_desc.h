@@ -14,7 +14,9 @@ constexpr int kThreads = 256;  // work-group size of the column-owner and combin
 constexpr int kRowThreads = 64;  // narrow row-owner kernels: one wavefront per tile
 constexpr int kWideCols = 8;     // from this many compiled columns on, row tiles stage Q in LDS
 constexpr int kWideLdsBytes = 48 * 1024;  // LDS budget of a wide row tile's Q slice
-constexpr int kMfmaRowBlocks = 4;  // matrix-core row tiles: blocks of 16 rows per wavefront
+constexpr int kMfmaRowBlocks = 2;  // matrix-core row tiles: blocks of 16 rows per wavefront
+constexpr int kMfmaRowCols = 16;    // stacked columns from which row passes run on the matrix cores
+constexpr int kMfmaSegCols = 2048;  // matrix-core row tiles: longest column segment
 constexpr int kMfmaTileCols = 256;  // matrix-core column tiles: columns per tile (four wavefronts)
 
 // One stacked column of a (worker, layer) pair.
@@ -40,6 +42,8 @@ struct PairDesc {
     int32_t nblk;      // column-owner kernel: row blocks
     int32_t blk_rows;  // rows per block
     int32_t V;         // floats per vector load on this layer: 4, 2 or 1 (largest that divides q)
+    int32_t wc;        // matrix-core row tiles: wavefronts side by side over the column steps (1, 2 or 4)
+    int32_t pad;
 };
 
 // Row-owner tile: rows [row0, row0 + nrows) x column segment seg of one pair.

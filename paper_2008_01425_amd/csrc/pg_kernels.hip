@@ -486,211 +486,330 @@ __device__ __forceinline__ void ld4(const float *p, float (&x)[4]) {
 #pragma unroll
     for (int v = 0; v < 4; ++v) x[v] = t[v];
 }
+// The 64 columns of one row step as the 16 lanes lo see them: 4 / V loads of V floats in which
+// the lanes sit side by side; a lane's float t is column 16 V (t / V) + V lo + t % V of the step.
+// Addresses are a wavefront-uniform base plus a 32-bit byte offset per lane (a layer is smaller
+// than 4 GB), which is the form a load takes its base from scalar registers in.  `off` is the
+// byte offset of the step's first column in the row (always inside the row).  FULL: all 64
+// columns exist.  Otherwise `nvalid` columns are left in the row: units at or past that re-read
+// the first column (the caller discards or zeroes them) and are not stored.
 template <int V>
-__device__ __forceinline__ void ld4(const float *p, float (&x)[4]) {
-#pragma unroll
-    for (int u = 0; u < 4 / V; ++u) {
-        const typename VecT<V>::T t = ldg<V>(p + V * u);
-#pragma unroll
-        for (int v = 0; v < V; ++v) x[V * u + v] = t[v];
-    }
+__device__ __forceinline__ typename VecT<V>::T ldg_at(const float *base, uint32_t byte_off) {
+    return *(const PG_GLOBAL typename VecT<V>::T *)((const PG_GLOBAL char *)base + byte_off);
 }
 template <int V>
-__device__ __forceinline__ void ld4_edge(const float *p, int nvalid, float (&x)[4]) {
+__device__ __forceinline__ void stg_at(float *base, uint32_t byte_off, typename VecT<V>::T v) {
+    *(PG_GLOBAL typename VecT<V>::T *)((PG_GLOBAL char *)base + byte_off) = v;
+}
+template <int V, bool FULL>
+__device__ __forceinline__ void ldrow(const float *base, uint32_t off, int lo, int nvalid, float (&x)[4]) {
 #pragma unroll
     for (int u = 0; u < 4 / V; ++u) {
-        const bool ok = V * u < nvalid;
-        const typename VecT<V>::T t = ldg<V>(p + (ok ? V * u : nvalid - V));
+        const int c = 16 * V * u + V * lo;
+        const typename VecT<V>::T t = ldg_at<V>(base, off + 4u * (uint32_t)((FULL || c < nvalid) ? c : 0));
 #pragma unroll
-        for (int v = 0; v < V; ++v) x[V * u + v] = ok ? t[v] : 0.0f;
+        for (int e = 0; e < V; ++e) x[V * u + e] = t[e];
     }
 }
+template <int V, bool FULL>
+__device__ __forceinline__ void strow(float *base, uint32_t off, int lo, int nvalid, const float (&x)[4]) {
+#pragma unroll
+    for (int u = 0; u < 4 / V; ++u) {
+        const int c = 16 * V * u + V * lo;
+        typename VecT<V>::T t;
+#pragma unroll
+        for (int e = 0; e < V; ++e) t[e] = x[V * u + e];
+        if (FULL || c < nvalid) stg_at<V>(base, off + 4u * (uint32_t)c, t);
+    }
+}
+// The same lane-to-column map into an LDS row of 64 floats.
 template <int V>
-__device__ __forceinline__ void st4_edge(float *p, int nvalid, const float (&x)[4]) {
+__device__ __forceinline__ void lds_put_row(float *row, int lo, const float (&x)[4]) {
 #pragma unroll
     for (int u = 0; u < 4 / V; ++u) {
         typename VecT<V>::T t;
 #pragma unroll
-        for (int v = 0; v < V; ++v) t[v] = x[V * u + v];
-        if (V * u < nvalid) stg<V>(p + V * u, t);
+        for (int e = 0; e < V; ++e) t[e] = x[V * u + e];
+        *reinterpret_cast<typename VecT<V>::T *>(row + 16 * V * u + V * lo) = t;
     }
 }
+// Orders one wavefront's LDS writes before its later LDS reads of other lanes' data (the LDS
+// serves a wavefront's instructions in order; this keeps the compiler from reordering them).
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
-// Row-owner pass on the matrix cores: one wavefront per tile of MB blocks of 16 rows by one
-// column segment, 16 columns per step.  Lane (lo, hi) holds X[row lo of the block][c + 4 hi + v],
-// v = 0..3.
-//   SWEEP : D[row][j] += X[row][c + 4 hi + v] * Q_j[c + 4 hi + v], one instruction per v
-//           (A = X, B = the stacked right-hand sides, j = lo);
-//   UPDATE: transposed, so that the result lands in the layout the values were loaded in:
-//           D[col][row] = X[row][col] - sum_j Q'_j[col] * (coef_j Phat_j[row]), four stacked
-//           columns j = 4 m + hi per instruction (A = -Q', B = coef * Phat, C = X);
-//   both  : the sweep multiplies the stored (rounded) values.
-// RCM = compiled stacked columns / 4 (2 or 4): the instructions one update block takes.
+// Row-owner pass on the matrix cores.  A tile is a block of rows by one column segment; it is
+// walked in steps of 64 columns.  Its four wavefronts are arranged WR x WC (WC = pd.wc): wavefront
+// (wr, wc) owns MB blocks of 16 rows and every WC-th step, so that the WC wavefronts of a row
+// group read adjacent 256-byte pieces of the same rows.  Loads and stores are coalesced: lane
+// (lo, hi) holds, for v = 0..3, four floats of row 4 v + hi of a block (column map of ldrow).
+//   UPDATE: D_t[row][slot] = X - sum_j (coef_j Phat_j[row]) Q'_j[col(slot, t)], four stacked
+//           columns j = 4 m + hi per instruction (A = coef * Phat, B = -Q', C = X); the result
+//           comes back in exactly the layout the values were loaded in (register v = row / 4);
+//   SWEEP : needs rows across the lanes lo, so the (updated, rounded) block goes through a
+//           private LDS buffer, 16 x 64 floats, and comes back as A[row][k]: lane (lo = row,
+//           hi = k) reads the four floats at column 16 s2 + 4 hi; the step's 64 x 16 slice of
+//           the right-hand sides is staged the same way as B[k][j] (layout [column / 4][j][4]).
+//           D[row][j] += X[row][c] Q_j[c], 16 instructions per block and step.
+// Partial sums of the WC wavefronts of a row group meet in LDS, in a fixed order.  Steps with
+// all 64 columns of a wavefront whose rows all exist run a body without any bounds handling.
+// RCM = compiled stacked columns / 4 (2 or 4): the instructions one update block takes per t.
+constexpr int kMrowXStride = 68;  // floats per LDS row: 64 + 4 keeps 128-bit reads down a column of lanes conflict-free
+constexpr int kMrowWaveFloats = 2 * 16 * kMrowXStride + 16 * 64;  // two X buffers and the Q slice of a step
+constexpr size_t kMrowLdsBytes = (size_t)(kThreads / 64) * kMrowWaveFloats * sizeof(float);
+template <bool B>
+struct BoolTag {
+    static constexpr bool value = B;
+};
+// Two work-groups per CU: left alone the compiler takes every register it can (one work-group).
 template <int V, int RCM, int MB, int D, bool UPDATE, bool SWEEP, bool GRAD>
-__global__ void __launch_bounds__(kRowThreads)
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
 mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, const PairDesc *__restrict__ pairs,
             const ColDesc *__restrict__ cols, float *const *__restrict__ xs,
             const float *__restrict__ qstate, const float *__restrict__ phat,
             double *__restrict__ pw, const float *const *__restrict__ gs, double eta) {
+    extern __shared__ double smem[];
     const RowTile t = tiles[blockIdx.x];
     const PairDesc pd = pairs[t.pair];
     float *X = xs[pd.worker] + pd.x_off;
     const float *Gp = GRAD ? gs[pd.worker] + pd.x_off : nullptr;
-    const int lane = threadIdx.x, lo = lane & 15, hi = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, lo = lane & 15, hi = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // the same for the whole wavefront: keep it scalar
+    float *lds = reinterpret_cast<float *>(smem) + wave * kMrowWaveFloats;
+    float *qbuf = lds + 2 * 16 * kMrowXStride;
     const int q = pd.q, R = pd.R;
+    const int WC = pd.wc;  // 1, 2 or 4
+    const int wcol = wave & (WC - 1);
+    const int wr = wave >> (WC == 4 ? 2 : (WC == 2 ? 1 : 0));
     const int c_begin = t.seg * pd.seg_len;
     const int c_end = min(q, c_begin + pd.seg_len);
-    const int nsteps = (c_end - c_begin + 15) >> 4;
-    const bool ragged = ((c_end - c_begin) & 15) != 0;
+    const int nst_all = (c_end - c_begin + 63) >> 6;
     const int row_end = t.row0 + t.nrows;
-    const int nrb = (t.nrows + 15) >> 4;  // blocks of 16 rows in this tile, at most MB
+    const int row0w = t.row0 + wr * 16 * MB;  // this wavefront's first row; none left: no steps
+    const int nsteps = (row0w < row_end && nst_all > wcol) ? (nst_all - wcol + WC - 1) / WC : 0;
 
-    bool rok[MB];
-    int64_t roff[MB];  // float offset of this lane's first element at column 0 of the segment
-    int rowi[MB];
+    // byte offsets of this lane's rows (a row past the tile's end stands in for by the last one)
+    uint32_t roff[MB][4];
 #pragma unroll
-    for (int b = 0; b < MB; ++b) {
-        const int r = t.row0 + 16 * b + lo;
-        rok[b] = r < row_end;
-        rowi[b] = rok[b] ? r : row_end - 1;
-        roff[b] = (int64_t)rowi[b] * q + 4 * hi;
-    }
-    // sweep operand B: stacked column lo at columns c + 4 hi + v
-    const float *qs = qstate + cols[pd.col0 + min(lo, R - 1)].q_off + 4 * hi;
-    // update operands: A = -Q'_j at column c + 4 (lo % 4) + lo / 4 (the column D's row index lo
-    // stands for), B = coef_j * Phat_j[row lo], both for j = 4 m + hi
-    const float *qu[RCM];
-    double cp[MB][RCM];
+    for (int b = 0; b < MB; ++b)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            roff[b][v] = 4u * (uint32_t)min(row0w + 16 * b + 4 * v + hi, row_end - 1) * (uint32_t)q;
+
+    // update operand A: coef_j * Phat_j[row lo of the block], j = 4 m + hi
+    const float *qup[UPDATE ? RCM : 1];
+    double cp[UPDATE ? MB : 1][UPDATE ? RCM : 1];
     if (UPDATE) {
 #pragma unroll
         for (int m = 0; m < RCM; ++m) {
             const int j = 4 * m + hi;
             const ColDesc cd = cols[pd.col0 + min(j, R - 1)];
-            qu[m] = qstate + cd.q_off + 4 * (lo & 3) + (lo >> 2);
+            qup[m] = qstate + cd.q_off;
             const double coef = (j < R) ? (double)cd.coef : 0.0;
 #pragma unroll
-            for (int b = 0; b < MB; ++b) cp[b][m] = coef * (double)ldg1(phat + cd.ph_off + rowi[b]);
+            for (int b = 0; b < MB; ++b)
+                cp[b][m] = coef * (double)ldg1(phat + cd.ph_off + min(row0w + 16 * b + lo, row_end - 1));
         }
+    }
+    // sweep: this lane stages the right-hand sides j = hi + 4 i (the update's j = 4 m + hi: when
+    // both run, one set of loads serves the two)
+    const float *qsp[SWEEP ? 4 : 1];
+    if (SWEEP && !UPDATE) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qsp[i] = qstate + cols[pd.col0 + min(hi + 4 * i, R - 1)].q_off;
     }
     mfma_acc acc[MB];
 #pragma unroll
     for (int b = 0; b < MB; ++b) acc[b] = mfma_acc{0.0, 0.0, 0.0, 0.0};
 
     struct Buf {
-        float x[MB][4];
-        float g[GRAD ? MB : 1][4];
-        float qs[4];
-        float qu[RCM];
+        float x[MB][4][4];
+        float g[GRAD ? MB : 1][4][4];
+        float qu[UPDATE ? RCM : 1][4];
+        float qs[(SWEEP && !UPDATE) ? 4 : 1][4];  // fused: the update's Q' slices are the same data, same lanes
     };
-    auto load = [&](int s, Buf &f) {
-        const int c = c_begin + 16 * s;
-        const bool edge = ragged && s == nsteps - 1;
-        const int nvalid = c_end - (c + 4 * hi);  // this lane's valid floats (may be <= 0 on the edge)
-        if (!edge) {
-            if (SWEEP) ld4<V>(qs + c, f.qs);
-#pragma unroll
-            for (int b = 0; b < MB; ++b)
-                if (b < nrb) ld4<V>(X + roff[b] + c, f.x[b]);
-            if (GRAD) {
-#pragma unroll
-                for (int b = 0; b < MB; ++b)
-                    if (b < nrb) ld4<V>(Gp + roff[b] + c, f.g[GRAD ? b : 0]);
-            }
-        } else {
-            if (SWEEP) ld4_edge<V>(qs + c, nvalid, f.qs);
-#pragma unroll
-            for (int b = 0; b < MB; ++b)
-                if (b < nrb) ld4_edge<V>(X + roff[b] + c, nvalid, f.x[b]);
-            if (GRAD) {
-#pragma unroll
-                for (int b = 0; b < MB; ++b)
-                    if (b < nrb) ld4_edge<V>(Gp + roff[b] + c, nvalid, f.g[GRAD ? b : 0]);
-            }
-        }
-        if (UPDATE) {
-            // past the right edge any column inside the segment will do: those results are not stored
-            const int cu = edge ? min(0, c_end - 1 - (c + 4 * (lo & 3) + (lo >> 2))) : 0;
-#pragma unroll
-            for (int m = 0; m < RCM; ++m) f.qu[m] = ldg1(qu[m] + c + cu);
-        }
-    };
-    auto process = [&](int s, Buf &f) {
-        const int c = c_begin + 16 * s;
-        const bool edge = ragged && s == nsteps - 1;
-        const int nvalid = edge ? c_end - (c + 4 * hi) : 4;
-        double qsd[4], qud[RCM];
-        if (SWEEP) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) qsd[v] = (double)f.qs[v];
-        }
-        if (UPDATE) {
-#pragma unroll
-            for (int m = 0; m < RCM; ++m) qud[m] = -(double)f.qu[m];
-        }
+    auto load = [&](auto full, int s, Buf &f) {
+        constexpr bool FULL = decltype(full)::value;
+        const int cs = c_begin + 64 * (wcol + WC * s);
+        const int nvalid = c_end - cs;
+        const uint32_t cso = 4u * (uint32_t)cs;
 #pragma unroll
         for (int b = 0; b < MB; ++b) {
-            if (b < nrb) {
-                mfma_acc d;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    d[v] = (double)f.x[b][v];
-                    if (GRAD) d[v] = fma(-eta, (double)f.g[GRAD ? b : 0][v], d[v]);
+            for (int v = 0; v < 4; ++v) {
+                ldrow<V, FULL>(X, roff[b][v] + cso, lo, nvalid, f.x[b][v]);
+                if (GRAD) ldrow<V, FULL>(Gp, roff[b][v] + cso, lo, nvalid, f.g[GRAD ? b : 0][v]);
+            }
+        }
+        if (UPDATE) {
+#pragma unroll
+            for (int m = 0; m < RCM; ++m) ldrow<V, FULL>(qup[m], cso, lo, nvalid, f.qu[UPDATE ? m : 0]);
+        }
+        if (SWEEP && !UPDATE) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ldrow<V, FULL>(qsp[i], cso, lo, nvalid, f.qs[(SWEEP && !UPDATE) ? i : 0]);
+        }
+    };
+    auto process = [&](auto full, int s, Buf &f) {
+        constexpr bool FULL = decltype(full)::value;
+        const int cs = c_begin + 64 * (wcol + WC * s);
+        const int nvalid = c_end - cs;
+        const uint32_t cso = 4u * (uint32_t)cs;
+        float bq[4][4];
+        if (SWEEP) {
+            // B[k][j]: layout [column / 4][j][4]; a unit of V floats stays inside one group of 4
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int u = 0; u < 4 / V; ++u) {
+                    const int c = 16 * V * u + V * lo;
+                    typename VecT<V>::T tv;
+#pragma unroll
+                    for (int e = 0; e < V; ++e)
+                        tv[e] = UPDATE ? f.qu[UPDATE ? (i < RCM ? i : RCM - 1) : 0][V * u + e]
+                                       : f.qs[(SWEEP && !UPDATE) ? i : 0][V * u + e];
+                    *reinterpret_cast<typename VecT<V>::T *>(qbuf + ((c >> 2) * 16 + hi + 4 * i) * 4 + (c & 3)) = tv;
                 }
-                if (UPDATE) {
+            }
+            wave_lds_sync();
 #pragma unroll
-                    for (int m = 0; m < RCM; ++m)
-                        if (4 * m < R) d = mfma16(qud[m], cp[b][m], d);
-                    float xn[4];
+            for (int s2 = 0; s2 < 4; ++s2) {
+                const VecT<4>::T tv = *reinterpret_cast<const VecT<4>::T *>(qbuf + ((4 * s2 + hi) * 16 + lo) * 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) bq[s2][e] = tv[e];
+            }
+        }
+        // columns past the row's end: the sweep must see zeros there
+        bool cok[4];
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) cok[tt] = FULL || 16 * V * (tt / V) + V * lo < nvalid;
+#pragma unroll
+        for (int b = 0; b < MB; ++b) {
+            if (UPDATE) {
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) {
+                    mfma_acc d;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        xn[v] = (float)d[v];
-                        d[v] = (v < nvalid) ? (double)xn[v] : 0.0;  // the sweep uses the stored (rounded) value
+                        d[v] = (double)f.x[b][v][tt];
+                        if (GRAD) d[v] = fma(-eta, (double)f.g[GRAD ? b : 0][v][tt], d[v]);
                     }
-                    if (rok[b]) st4_edge<V>(X + roff[b] + c, nvalid, xn);
-                }
-                if (SWEEP) {
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[b] = mfma16(d[v], qsd[v], acc[b]);
+                    for (int m = 0; m < RCM; ++m) d = mfma16(cp[b][m], -(double)f.qu[UPDATE ? m : 0][tt], d);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) f.x[b][v][tt] = cok[tt] ? (float)d[v] : 0.0f;
+                    PG_FENCE();  // keeps the conversions of later groups from being hoisted (registers)
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    if (FULL || row0w + 16 * b + 4 * v + hi < row_end)
+                        strow<V, FULL>(X, roff[b][v] + cso, lo, nvalid, f.x[b][v]);
+                }
+            }
+            if (SWEEP) {
+                if (!UPDATE && !FULL) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+#pragma unroll
+                        for (int tt = 0; tt < 4; ++tt) f.x[b][v][tt] = cok[tt] ? f.x[b][v][tt] : 0.0f;
+                }
+                float *xb = lds + (b & 1) * 16 * kMrowXStride;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) lds_put_row<V>(xb + (4 * v + hi) * kMrowXStride, lo, f.x[b][v]);
+                wave_lds_sync();
+#pragma unroll
+                for (int s2 = 0; s2 < 4; ++s2) {
+                    const VecT<4>::T av =
+                        *reinterpret_cast<const VecT<4>::T *>(xb + lo * kMrowXStride + 16 * s2 + 4 * hi);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[b] = mfma16((double)av[e], (double)bq[s2][e], acc[b]);
+                    PG_FENCE();
                 }
             }
         }
     };
-
-    // software pipeline: loads of step s + D are issued before the arithmetic of step s
-    constexpr int NB = D + 1;
-    Buf ring[NB];
+    // software pipeline over steps [0, n): loads of step s + D are issued before the arithmetic of step s
+    auto pipeline = [&](auto full, int n) {
+        constexpr int NB = D + 1;
+        Buf ring[NB];
 #pragma unroll
-    for (int k = 0; k < D; ++k)
-        if (k < nsteps) load(k, ring[k]);
-    int s = 0;
-    for (; s + NB + D <= nsteps; s += NB) {
+        for (int k = 0; k < D; ++k)
+            if (k < n) load(full, k, ring[k]);
+        int s = 0;
+        for (; s + NB + D <= n; s += NB) {
 #pragma unroll
-        for (int k = 0; k < NB; ++k) {
-            load(s + k + D, ring[(k + D) % NB]);
-            PG_FENCE();
-            process(s + k, ring[k]);
-            PG_FENCE();
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < NB + D - 1; ++k) {
-        if (s + k < nsteps) {
-            if (s + k + D < nsteps) load(s + k + D, ring[(k + D) % NB]);
-            PG_FENCE();
-            process(s + k, ring[k % NB]);
-            PG_FENCE();
-        }
-    }
-
-    if (SWEEP && lo < R) {
-        double *dst = pw + pd.pw_off + ((int64_t)t.seg * R + lo) * pd.p;
-#pragma unroll
-        for (int b = 0; b < MB; ++b)
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const int r = t.row0 + 16 * b + 4 * w + hi;
-                if (r < row_end) dst[r] = acc[b][w];
+            for (int k = 0; k < NB; ++k) {
+                load(full, s + k + D, ring[(k + D) % NB]);
+                PG_FENCE();
+                process(full, s + k, ring[k]);
+                PG_FENCE();
             }
+        }
+#pragma unroll
+        for (int k = 0; k < NB + D - 1; ++k) {
+            if (s + k < n) {
+                if (s + k + D < n) load(full, s + k + D, ring[(k + D) % NB]);
+                PG_FENCE();
+                process(full, s + k, ring[k % NB]);
+                PG_FENCE();
+            }
+        }
+    };
+
+    // The segment's last step may be ragged; it is the last step of the wavefront that owns it.
+    const bool ragged_mine = ((c_end - c_begin) & 63) != 0 && ((nst_all - 1) & (WC - 1)) == wcol;
+    if (row0w + 16 * MB <= row_end) {
+        const int nfull = ragged_mine ? nsteps - 1 : nsteps;
+        pipeline(BoolTag<true>(), nfull);
+        if (nfull < nsteps) {
+            Buf last;
+            load(BoolTag<false>(), nsteps - 1, last);
+            process(BoolTag<false>(), nsteps - 1, last);
+        }
+    } else {
+        // a wavefront with rows past the tile's end: a few tiles per layer, no prefetch ring
+        for (int s = 0; s < nsteps; ++s) {
+            Buf one;
+            load(BoolTag<false>(), s, one);
+            process(BoolTag<false>(), s, one);
+        }
+    }
+
+    if (SWEEP) {
+        // D[row][j] sits in lane (lo = j, hi = row % 4), register row / 4
+        if (WC > 1) {
+            double *mine = reinterpret_cast<double *>(lds);
+            wave_lds_sync();
+            if (wcol != 0) {
+#pragma unroll
+                for (int b = 0; b < MB; ++b)
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) mine[(b * 4 + w) * 64 + lane] = acc[b][w];
+            }
+            __syncthreads();
+            if (wcol == 0) {
+                for (int o = 1; o < WC; ++o) {
+                    const double *other = reinterpret_cast<const double *>(lds + o * kMrowWaveFloats);
+#pragma unroll
+                    for (int b = 0; b < MB; ++b)
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) acc[b][w] += other[(b * 4 + w) * 64 + lane];
+                }
+            }
+        }
+        if (wcol == 0 && lo < R) {
+            double *dst = pw + pd.pw_off + ((int64_t)t.seg * R + lo) * pd.p;
+#pragma unroll
+            for (int b = 0; b < MB; ++b)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const int r = row0w + 16 * b + 4 * w + hi;
+                    if (r < row_end) dst[r] = acc[b][w];
+                }
+        }
     }
 }
 
@@ -713,7 +832,7 @@ mcol_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
     const float *X = xs[pd.worker] + pd.x_off;
     const int lane = threadIdx.x & 63, lo = lane & 15, hi = lane >> 4;
     const int q = pd.q, R = pd.R;
-    const int c0 = t.c0 + 64 * (int)(threadIdx.x >> 6);
+    const int c0 = t.c0 + 64 * __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if (c0 >= q) return;
     const int ncols = min(64, q - c0);  // this wavefront's columns inside the matrix
     const int rb = t.blk * pd.blk_rows;

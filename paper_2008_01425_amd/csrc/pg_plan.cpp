@@ -38,7 +38,6 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     P.n_layers = n_layers;
     P.rank = rank;
     P.steps = power_steps;
-    P.mfma_rows = tune.mfma_rows;
     P.mfma_cols = tune.mfma_cols;
     P.edges.assign(edges, edges + 2 * (size_t)n_edges);
     P.edge_w.assign(edge_w, edge_w + n_edges);
@@ -122,7 +121,9 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     // ---- per-layer launch geometry ----
     struct Geo {
         int lpr, nseg, seg_len, rows_iter_base;  // row-owner
+        int wc;                                  // matrix-core row tiles: wavefronts across the column steps
         bool wide;                               // row-owner: many stacked columns, Q slice in LDS
+        bool mrow;                               // row-owner: matrix-core tiles
         int lg, nblk, blk_rows;                  // column-owner
     };
     std::vector<Geo> geo(n_layers);
@@ -136,9 +137,12 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         for (int i = 0; i < n_workers; ++i) max_deg = std::max(max_deg, P.incident[i].size());
         int rc_max = compiled_cols(std::max<int>(1, (int)max_deg * L.r));
         g.wide = rc_max >= kWideCols;
+        // Row passes on the matrix cores pay from 16 stacked columns on (measured: at 8 the vector
+        // kernels' P-sweep is the faster one) and address a layer with 32-bit byte offsets.
+        g.mrow = tune.mfma_rows && rc_max >= kMfmaRowCols && (int64_t)L.p * L.q < ((int64_t)1 << 30);
         // Lanes per row: a whole wavefront for few stacked columns; 16 for many, where the
         // per-row lane reduction (RC values per row) would otherwise rival the products.
-        g.lpr = std::min((g.wide && !tune.mfma_rows) ? 16 : 64, pow2_ceil(nv));
+        g.lpr = std::min((g.wide && !g.mrow) ? 16 : 64, pow2_ceil(nv));
         int chunk = g.lpr * L.V;  // floats one lane group covers per step
         int nchunks = (L.q + chunk - 1) / chunk;
         int seg_chunks;
@@ -149,12 +153,11 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             int64_t chunk_bytes = (int64_t)rows_iter * chunk * 4;
             seg_chunks = (int)std::max<int64_t>(1, tn.row_tile_bytes / chunk_bytes);
             g.rows_iter_base = 64 / g.lpr;
-        } else if (tune.mfma_rows) {
-            // matrix cores: one wavefront per tile of 16 * kMfmaRowBlocks rows, 16 columns a step
-            chunk = 16;
+        } else if (g.mrow) {
+            // matrix cores: steps of 64 columns; a row is cut only when it is very long
+            chunk = 64;
             nchunks = (L.q + chunk - 1) / chunk;
-            int64_t chunk_bytes = (int64_t)16 * kMfmaRowBlocks * chunk * 4;
-            seg_chunks = (int)std::max<int64_t>(1, tn.wide_tile_bytes / 2 / chunk_bytes);
+            seg_chunks = kMfmaSegCols / chunk;
             g.rows_iter_base = 64 / g.lpr;  // for this layer's workers with few stacked columns
         } else {
             // four wavefronts per tile share the Q slice in LDS: RC * seg_len floats must fit
@@ -165,6 +168,8 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         seg_chunks = (nchunks + g.nseg - 1) / g.nseg;
         g.nseg = (nchunks + seg_chunks - 1) / seg_chunks;
         g.seg_len = seg_chunks * chunk;
+        g.wc = 1;
+        if (g.mrow) g.wc = seg_chunks >= 4 ? 4 : (seg_chunks >= 2 ? 2 : 1);
 
         // Column-owner kernel: lanes side by side over columns; pick the lane-group width that
         // wastes the fewest lanes on the ragged end of a row (ties go to the wider group).
@@ -223,6 +228,8 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             pd.nblk = g.nblk;
             pd.blk_rows = g.blk_rows;
             pd.V = L.V;
+            pd.wc = g.wc;
+            pd.pad = 0;
             pwo += (int64_t)g.nseg * pd.R * L.p;
             qwo += (int64_t)g.nblk * pd.R * L.q;
             for (int e : P.incident[i])
@@ -317,11 +324,11 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     P.isolated_pairs.clear();
     P.isolated_elems = 0;
     // many stacked columns: one class (one kernel instantiation) per vector width
-    auto row_class = [&](int RC, int V) -> size_t {
+    auto row_class = [&](int RC, int V, bool mfma) -> size_t {
         if (RC < kWideCols) V = 0;
         for (size_t k = 0; k < P.row_classes.size(); ++k)
-            if (P.row_classes[k].RC == RC && P.row_classes[k].V == V) return k;
-        P.row_classes.push_back({RC, V, {}, 0, 0, 0});
+            if (P.row_classes[k].RC == RC && P.row_classes[k].V == V && P.row_classes[k].mfma == mfma) return k;
+        P.row_classes.push_back({RC, V, mfma, {}, 0, 0, 0});
         return P.row_classes.size() - 1;
     };
     auto col_class = [&](int RC, int V) -> size_t {
@@ -343,7 +350,8 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
                 continue;
             }
             int RC = compiled_cols(pd.R);
-            RowClass &rc = P.row_classes[row_class(RC, L.V)];
+            const bool mrow = g.mrow && RC >= kWideCols;
+            RowClass &rc = P.row_classes[row_class(RC, L.V, mrow)];
             int rows_iter = g.rows_iter_base * rows_unroll(RC);
             int tile_rows;
             if (RC < kWideCols) {
@@ -353,8 +361,8 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
                     iters = (int)std::max<int64_t>(1, tn.row_tile_bytes / bytes_iter);
                 }
                 tile_rows = rows_iter * iters;
-            } else if (tune.mfma_rows) {
-                tile_rows = 16 * kMfmaRowBlocks;
+            } else if (mrow) {
+                tile_rows = 16 * kMfmaRowBlocks * (4 / g.wc);
             } else {
                 // enough rows that staging the Q slice (RC rows' worth of traffic) is amortised
                 int64_t seg_bytes = (int64_t)std::min(g.seg_len, L.q) * 4;

@@ -20,6 +20,7 @@ struct LayerInfo {
 struct RowClass {
     int RC;
     int V;                  // 0: any vector width (RC < kWideCols); else the one width of this class
+    bool mfma;              // tiles cut for the matrix-core row kernel
     std::vector<RowTile> tiles;
     size_t dev_first = 0;   // index of the first tile in the uploaded table
     double elems = 0;       // parameter elements covered (for byte accounting)
@@ -40,12 +41,12 @@ struct Tuning {
     int wide_tile_bytes = 256 * 1024; // target parameter bytes per wide row-owner tile (four wavefronts)
     // 8-16 stacked columns: which passes run on the matrix cores
     bool mfma_cols = true;            // Q-sweep
-    bool mfma_rows = false;           // P-sweep and update
+    bool mfma_rows = true;            // P-sweep and update (layers with 16 stacked columns)
 };
 
 struct Plan {
     int n = 0, n_edges = 0, n_layers = 0, rank = 0, steps = 0;
-    bool mfma_rows = false, mfma_cols = true; // passes over 8-16 stacked columns that run on the matrix cores
+    bool mfma_cols = true;                   // Q-sweep over 8-16 stacked columns runs on the matrix cores
     std::vector<int32_t> edges;   // 2 * n_edges
     std::vector<float> edge_w;
     std::vector<LayerInfo> layers;

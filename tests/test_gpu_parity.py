@@ -89,6 +89,19 @@ def test_irregular_graph_with_isolated_and_leaf_workers():
     _check(wl, 2, TOL_10, fused=True)
 
 
+def test_sixteen_stacked_columns_mixed_degrees_and_odd_shapes():
+    """Rank 4 on a star with a chord: workers with 16, 8, 8, 4 and 4 stacked columns share every
+    layer (matrix-core and vector kernels side by side); odd, short and just-over-a-step row
+    lengths, row counts around the 16-row blocks."""
+    edges = [[0, 1], [0, 2], [3, 0], [0, 4], [2, 1]]
+    shapes = [(50, 131), (17, 70), (100, 64), (9, 3), (33, 200), (16, 65), (1, 40)]
+    wl = _custom("star16", 5, edges, [0.2, 0.2, 0.2, 0.2, 0.15], shapes, 4, 2)
+    _check(wl, 1, TOL_1)
+    _check(wl, 3, TOL_10, fused=True)
+    wl = _custom("star16_sgd", 5, edges, [0.2, 0.2, 0.2, 0.2, 0.15], shapes, 4, 1)
+    _check_sgd(wl, [0.1, 0.05], TOL_10)
+
+
 def test_many_tiles_and_tail_rows():
     wl = _custom("tall", 3, W.ring_edges(3), 1 / 3, [(4099, 68), (1031, 516), (70, 4612)], 2, 1)
     _check(wl, 1, TOL_1)

@@ -7,6 +7,9 @@
 // Two streaming kernel families cover the passes over X:
 //   row_kernel  -- a lane group owns rows: P-sweep (X S), rank-r update, or both fused;
 //   col_kernel  -- a lane owns columns:    Q-sweep (X^T T).
+// With up to 4 stacked columns the vector ALUs keep up with HBM.  From 8 on (row_wide_kernel)
+// they fall behind, and at 8 (Q-sweep) or 16 (all passes) the contraction moves to the double
+// precision matrix cores: mrow_kernel, mcol_kernel.
 // Small kernels work per edge: orth_gram_kernel / orth_kernel (combine + Gram-Schmidt) and comb_kernel.
 #include <hip/hip_runtime.h>
 #include <float.h>

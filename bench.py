@@ -22,12 +22,12 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 
 # Bytes that crossed the L2 -> fabric boundary per launch of a kernel kind, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs of this script, each scaled by the same counter's reading for a plain
-# 512 MiB device copy (factors 2.000 and 1.000); see profiles/vgg16_r1_traffic_counters.txt.
+# device copy of known size (factors 2.000 and 1.000); see profiles/vgg16_r1_traffic_counters.txt.
 MEASURED_TRAFFIC_BYTES = {
-    ("vgg16_r1", "update_sweep_p"): 960.1e6 + 943.6e6,
-    ("vgg16_r1", "update"): 964.2e6 + 941.8e6,
-    ("vgg16_r1", "update_sgd"): 1926.8e6 + 941.8e6,
-    ("vgg16_r1", "sweep_p"): 958.7e6 + 1.7e6,
+    ("vgg16_r1", "update_sweep_p"): 960.2e6 + 943.6e6,
+    ("vgg16_r1", "update"): 963.8e6 + 941.8e6,
+    ("vgg16_r1", "update_sgd"): 1903.2e6 + 941.8e6,
+    ("vgg16_r1", "sweep_p"): 958.8e6 + 1.7e6,
     ("vgg16_r1", "sweep_q"): 945.9e6 + 8.7e6,
 }
 

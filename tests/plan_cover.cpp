@@ -1,0 +1,168 @@
+// Host-only check of the planner (no HIP): for a list of problems, every (worker, layer) pair
+// with edges is covered exactly once by its row tiles (rows x column segments) and by its
+// column tiles (columns x row blocks), tiles respect what their kernel family assumes, and the
+// workspace sections hold the partial sums.  Prints "ok <name>" per problem; exit status 1 on
+// the first violation.  Built and run by tests/test_host_api.py.
+#include <cstdio>
+#include <algorithm>
+#include <map>
+#include <vector>
+
+#include "../include/powergossip.h"
+#include "../paper_2008_01425_amd/csrc/pg_plan.hpp"
+
+using namespace pg;
+
+#define REQUIRE(cond, ...)                       \
+    do {                                         \
+        if (!(cond)) {                           \
+            printf("FAIL %s: ", name);           \
+            printf(__VA_ARGS__);                 \
+            printf(" [%s]\n", #cond);            \
+            return 1;                            \
+        }                                        \
+    } while (0)
+
+static void ring(int n, std::vector<int32_t> &e) {
+    for (int i = 0; i < n; ++i) {
+        e.push_back(i);
+        e.push_back((i + 1) % n);
+    }
+}
+static void torus(int R, int C, std::vector<int32_t> &e) {
+    for (int r = 0; r < R; ++r)
+        for (int c = 0; c < C; ++c) {
+            int v = r * C + c;
+            e.push_back(v);
+            e.push_back(r * C + (c + 1) % C);
+            e.push_back(v);
+            e.push_back(((r + 1) % R) * C + c);
+        }
+}
+
+static int check(const char *name, int n, const std::vector<int32_t> &e, const std::vector<float> &ew,
+                 const std::vector<int32_t> &rows, const std::vector<int32_t> &cols, int rank, int steps,
+                 const Tuning &tune) {
+    Plan P;
+    int rc = build_plan(P, n, (int)ew.size(), e.data(), ew.data(), (int)rows.size(), rows.data(), cols.data(),
+                        rank, steps, tune);
+    REQUIRE(rc == PG_OK, "build_plan returned %d", rc);
+    const int L = (int)rows.size();
+
+    // ---- row tiles: per (pair, segment) the row intervals tile [0, p) ----
+    std::map<std::pair<int, int>, std::vector<std::pair<int, int>>> rcover;
+    for (const RowClass &c : P.row_classes)
+        for (const RowTile &t : c.tiles) {
+            REQUIRE(t.pair >= 0 && t.pair < (int)P.pairs.size(), "row tile pair %d", t.pair);
+            const PairDesc &pd = P.pairs[t.pair];
+            REQUIRE(compiled_cols(pd.R) == c.RC, "pair %d with R=%d in class RC=%d", t.pair, pd.R, c.RC);
+            REQUIRE(t.nrows >= 1 && t.row0 >= 0 && t.row0 + t.nrows <= pd.p, "row tile rows %d+%d of %d", t.row0, t.nrows, pd.p);
+            REQUIRE(t.seg >= 0 && t.seg < pd.nseg && (int64_t)t.seg * pd.seg_len < pd.q, "segment %d", t.seg);
+            if (c.RC >= kWideCols) REQUIRE(c.V == pd.V, "class V=%d, layer V=%d", c.V, pd.V);
+            if (c.mfma) {
+                REQUIRE(pd.wc == 1 || pd.wc == 2 || pd.wc == 4, "wc=%d", pd.wc);
+                REQUIRE(pd.seg_len % 64 == 0, "seg_len=%d", pd.seg_len);
+                REQUIRE(t.nrows <= 16 * kMfmaRowBlocks * (4 / pd.wc), "matrix-core tile of %d rows, wc=%d", t.nrows, pd.wc);
+                REQUIRE((int64_t)pd.p * pd.q < ((int64_t)1 << 30), "layer too large for 32-bit offsets");
+            } else if (c.RC >= kWideCols) {
+                REQUIRE((int64_t)c.RC * pd.seg_len * 4 <= kWideLdsBytes, "Q slice of %d x %d floats", c.RC, pd.seg_len);
+                REQUIRE(c.max_seg >= pd.seg_len, "max_seg");
+                REQUIRE(pd.seg_len % (pd.lpr * pd.V) == 0, "seg_len %d, lpr %d, V %d", pd.seg_len, pd.lpr, pd.V);
+            } else {
+                REQUIRE(pd.lpr >= 1 && pd.lpr <= 64 && (pd.lpr & (pd.lpr - 1)) == 0, "lpr=%d", pd.lpr);
+                REQUIRE(pd.seg_len % pd.V == 0, "seg_len %d V %d", pd.seg_len, pd.V);
+            }
+            rcover[{t.pair, t.seg}].push_back({t.row0, t.row0 + t.nrows});
+        }
+    // ---- column tiles: per (pair, row block) the column intervals tile [0, q) ----
+    std::map<std::pair<int, int>, std::vector<std::pair<int, int>>> ccover;
+    for (const ColClass &c : P.col_classes)
+        for (const ColTile &t : c.tiles) {
+            REQUIRE(t.pair >= 0 && t.pair < (int)P.pairs.size(), "col tile pair %d", t.pair);
+            const PairDesc &pd = P.pairs[t.pair];
+            REQUIRE(compiled_cols(pd.R) == c.RC, "pair %d with R=%d in column class RC=%d", t.pair, pd.R, c.RC);
+            REQUIRE(t.blk >= 0 && t.blk < pd.nblk && (int64_t)t.blk * pd.blk_rows < pd.p, "row block %d", t.blk);
+            const int cw = (c.RC >= kWideCols && P.mfma_cols) ? kMfmaTileCols : pd.lg * pd.V;
+            REQUIRE(t.c0 >= 0 && t.c0 < pd.q && t.c0 % cw == 0, "column tile at %d, width %d", t.c0, cw);
+            if (!(c.RC >= kWideCols && P.mfma_cols)) REQUIRE(c.max_rows >= pd.blk_rows, "max_rows");
+            ccover[{t.pair, t.blk}].push_back({t.c0, std::min(pd.q, t.c0 + cw)});
+        }
+    auto tiles_exactly = [](std::vector<std::pair<int, int>> v, int end) {
+        std::sort(v.begin(), v.end());
+        int at = 0;
+        for (auto &iv : v) {
+            if (iv.first != at) return false;
+            at = iv.second;
+        }
+        return at == end;
+    };
+    int64_t pw_need = 0, qw_need = 0;
+    for (int l = 0; l < L; ++l)
+        for (int i = 0; i < n; ++i) {
+            const int pair = l * n + i;
+            const PairDesc &pd = P.pairs[pair];
+            REQUIRE(pd.p == rows[l] && pd.q == cols[l] && pd.worker == i, "pair %d fields", pair);
+            REQUIRE(pd.R == (int)P.incident[i].size() * P.layers[l].r, "R of pair %d", pair);
+            if (pd.R == 0) {
+                REQUIRE(!rcover.count({pair, 0}) && !ccover.count({pair, 0}), "tiles for a worker without edges");
+                continue;
+            }
+            REQUIRE((int64_t)pd.nseg * pd.seg_len >= pd.q && (int64_t)(pd.nseg - 1) * pd.seg_len < pd.q, "segments of pair %d", pair);
+            REQUIRE((int64_t)pd.nblk * pd.blk_rows >= pd.p && (int64_t)(pd.nblk - 1) * pd.blk_rows < pd.p, "blocks of pair %d", pair);
+            for (int sg = 0; sg < pd.nseg; ++sg)
+                REQUIRE(tiles_exactly(rcover[{pair, sg}], pd.p), "rows of pair %d (layer %d, worker %d), segment %d", pair, l, i, sg);
+            for (int b = 0; b < pd.nblk; ++b)
+                REQUIRE(tiles_exactly(ccover[{pair, b}], pd.q), "columns of pair %d, block %d", pair, b);
+            REQUIRE(pd.pw_off == pw_need && pd.qw_off == qw_need, "partial-sum offsets of pair %d", pair);
+            pw_need += (int64_t)pd.nseg * pd.R * pd.p;
+            qw_need += (int64_t)pd.nblk * pd.R * pd.q;
+        }
+    REQUIRE(P.ws_qw >= P.ws_pw + (size_t)pw_need * 8, "P partial sums do not fit their section");
+    REQUIRE(P.ws_pd >= P.ws_qw + (size_t)qw_need * 8, "Q partial sums do not fit their section");
+    REQUIRE(P.ws_bytes >= P.ws_uq, "workspace size");
+    printf("ok %s\n", name);
+    return 0;
+}
+
+int main() {
+    int bad = 0;
+    std::vector<Tuning> tunings(3);
+    tunings[1].mfma_rows = false;
+    tunings[2].mfma_rows = false;
+    tunings[2].mfma_cols = false;
+    for (const Tuning &tn : tunings) {
+        std::vector<int32_t> e;
+        ring(4, e);
+        bad |= check("tiny", 4, e, std::vector<float>(4, 1 / 3.f), {64, 32, 16}, {32, 16, 1}, 1, 1, tn);
+        e.clear();
+        ring(16, e);
+        bad |= check("vgg16 r=2", 16, e, std::vector<float>(16, 1 / 3.f),
+                     {64, 64, 128, 128, 256, 256, 256, 512, 512, 512, 512, 512, 512, 10},
+                     {27, 576, 576, 1152, 1152, 2304, 2304, 2304, 4608, 4608, 4608, 4608, 4608, 512}, 2, 1, tn);
+        e.clear();
+        torus(4, 4, e);
+        bad |= check("lstm", 16, e, std::vector<float>(32, 0.2f), {33278, 2600, 2600, 2600, 2600},
+                     {650, 650, 650, 650, 650}, 4, 2, tn);
+        e.clear();
+        torus(8, 8, e);
+        {
+            std::vector<int32_t> r, c;
+            for (int i = 0; i < 161; ++i) {
+                r.push_back(64 + i * 13 % 2000);
+                c.push_back(i % 3 == 0 ? 1 : (i % 5 == 0 ? 147 : 64 * (1 + i % 70)));
+            }
+            bad |= check("resnet50-like", 64, e, std::vector<float>(128, 0.2f), r, c, 2, 2, tn);
+        }
+        e.clear();
+        ring(3, e);
+        bad |= check("odd shapes", 3, e, std::vector<float>(3, 1 / 3.f), {1, 7, 33278, 5, 4099}, {1, 3, 650, 100003, 68}, 3, 1, tn);
+        // star with a chord, rank 4: 16, 8, 8, 4 and 4 stacked columns in every layer; one worker without edges
+        e = {0, 1, 0, 2, 3, 0, 0, 4, 2, 1};
+        bad |= check("mixed degrees", 6, e, {0.2f, 0.2f, 0.2f, 0.2f, 0.15f},
+                     {50, 17, 100, 9, 33, 16, 1, 300, 2}, {131, 70, 64, 3, 200, 65, 40, 5000, 9}, 4, 2, tn);
+        e.clear();
+        torus(3, 3, e);
+        bad |= check("torus 3x3 rank 2", 9, e, std::vector<float>(18, 0.2f), {120, 33, 40, 2600}, {260, 12, 1, 63}, 2, 1, tn);
+    }
+    return bad;
+}

@@ -183,3 +183,19 @@ def test_plan_with_mixed_degrees_in_one_layer():
     assert B.pg_message_floats(ctx) == sum(min(4, p, q) * (p + q) for p, q in shapes)
     assert B.pg_workspace_bytes(ctx) > 0
     B.pg_destroy(ctx)
+
+
+def test_planner_tiles_cover_every_matrix_exactly_once(tmp_path):
+    """tests/plan_cover.cpp links the host planner alone (no HIP) and checks, for the benchmark
+    shapes, odd shapes and mixed degrees, in each kernel-family setting: row tiles x segments and
+    column tiles x row blocks partition every matrix, tiles respect their kernels' limits, partial
+    sums fit the workspace."""
+    import subprocess
+    exe = str(tmp_path / "plan_cover")
+    src = [os.path.join(ROOT, "tests", "plan_cover.cpp"),
+           os.path.join(ROOT, "paper_2008_01425_amd", "csrc", "pg_plan.cpp")]
+    build = subprocess.run(["g++", "-O1", "-std=c++17", "-o", exe] + src, capture_output=True, text=True, timeout=300)
+    assert build.returncode == 0, build.stderr[-3000:]
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert run.returncode == 0, run.stdout[-3000:]
+    assert run.stdout.count("ok ") == 21 and "FAIL" not in run.stdout

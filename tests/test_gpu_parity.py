@@ -102,6 +102,18 @@ def test_sixteen_stacked_columns_mixed_degrees_and_odd_shapes():
     _check_sgd(wl, [0.1, 0.05], TOL_10)
 
 
+@pytest.mark.parametrize("n,edges,w,rank", [
+    (2, [[0, 1]], 0.3, 16),                 # one edge at the largest rank: column-by-column Gram-Schmidt
+    (3, [[0, 1], [1, 2]], 0.4, 8),          # path: 8, 16 and 8 stacked columns
+    (3, [[0, 1], [2, 1]], 0.3, 6),          # ranks between the compiled sizes
+])
+def test_high_ranks(n, edges, w, rank):
+    shapes = [(70, 90), (40, 200), (24, 17), (12, 300), (5, 64)]
+    wl = _custom(f"rank{rank}_n{n}", n, edges, w, shapes, rank, 2, sigma=0.1)
+    _check(wl, 1, TOL_1)
+    _check(wl, 3, TOL_10, fused=True)
+
+
 def test_many_tiles_and_tail_rows():
     wl = _custom("tall", 3, W.ring_edges(3), 1 / 3, [(4099, 68), (1031, 516), (70, 4612)], 2, 1)
     _check(wl, 1, TOL_1)

@@ -278,6 +278,10 @@ def test_single_iterations_ragged_ring(rank):
 def test_single_iterations_with_gradients_on_a_torus():
     wl = _custom("iter_torus", 9, W.torus_edges(3, 3), 1 / 5, [(120, 260), (33, 12), (40, 1)], 2, 1)
     _check_iterate(wl, [1, 1, 2], TOL_10, eta=0.05)
+    # rank 4: 16 stacked columns (matrix-core row and column passes on the alternate buffers)
+    wl = _custom("iter_torus_r4", 9, W.torus_edges(3, 3), 1 / 5, [(120, 262), (33, 12), (40, 1)], 4, 1)
+    _check_iterate(wl, [1, 1, 2], TOL_10, eta=0.05)
+    _check_iterate(wl, [1, 1], TOL_10)
 
 
 def test_two_iterations_match_one_power_step_on_the_gpu():

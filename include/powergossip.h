@@ -197,7 +197,10 @@ int pg_iterate(pg_ctx *ctx, float *const *worker_params, float *q_state, float *
  * `rounds` consecutive gossip rounds with nothing touching the parameters in between
  * (the pure consensus iteration, Eq. (4)).  Same result as calling pg_round `rounds` times;
  * the update of round t and the first product of round t+1 share one pass over the
- * parameters.  rounds >= 0.
+ * parameters.  rounds >= 0.  Once a call has seen the same worker_params pointers (the first
+ * call with a new set copies the pointer table to the device and waits for the stream), a call
+ * with profiling off only launches kernels: it may be recorded into a HIP graph on a capturing
+ * stream and replayed.
  */
 int pg_run(pg_ctx *ctx, float *const *worker_params, float *q_state, void *workspace,
            void *hip_stream, int rounds);

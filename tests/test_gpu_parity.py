@@ -401,6 +401,32 @@ def test_run_equals_repeated_round_bitwise():
     a.close(); b.close()
 
 
+def test_run_can_be_captured_in_a_graph_and_replayed():
+    """After its first call pg_run only launches kernels, so a caller may capture it in a HIP
+    graph.  Every replay (with eager work and synchronisation in between) must leave exactly
+    what the same number of eager rounds leaves."""
+    import torch
+    wl = _custom("graph", 9, W.torus_edges(3, 3), 1 / 5, [(96, 260), (50, 1), (31, 27), (40, 130)], 2, 2)
+    eager, cap = _gb(wl), _gb(wl)
+    cap.run(1)          # first call: uploads the pointer table (not capturable), then rounds
+    eager.run(1)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        cap.run(3)
+    torch.cuda.synchronize()
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for rep in range(4):                    # the capture itself executed nothing
+        g.replay()
+        eager.run(3)
+        torch.cuda.synchronize()
+        for i in range(9):
+            assert np.array_equal(cap.x[i].cpu().numpy(), eager.x[i].cpu().numpy()), f"replay {rep}, worker {i}"
+        assert np.array_equal(cap.q.cpu().numpy(), eager.q.cpu().numpy()), f"replay {rep}, state"
+        scratch.add_(1.0).sum().item()      # unrelated eager work and a synchronisation between replays
+    eager.close(); cap.close()
+
+
 # ------------------------------------------------------------------ full-size configurations
 def test_vgg16_full_size_one_round_rank1():
     _check(W.get("vgg16_r1"), 1, TOL_1)

@@ -46,7 +46,10 @@ struct pg_ctx {
     float **d_gs = nullptr;
     std::vector<const float *> gs_cached;
     bool profiling = false;
-    int col_reverse = 1;
+    // Passes alternate direction through the parameters: each starts where the one before it
+    // (also the last one of an earlier call) ended, on data still in the memory-side cache.
+    bool alternate = true;
+    int reverse = 0;  // direction of the next pass
     std::vector<ProfRec> recs;
     std::vector<hipEvent_t> free_events;
 };
@@ -165,11 +168,11 @@ struct Launcher {
         const RowTile *tiles = c->d_row_tiles + rc.dev_first;
         if constexpr (RC < kWideCols) {
             row_kernel<RC, kRowsPerGroup, kPrefetchSteps, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
-                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
+                tiles, n, c->reverse, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
         } else if (rc.mfma) {
 #define PG_MROW(VV) mrow_kernel<VV, RC / 4, kMfmaRowBlocks, kMfmaRowPrefetch, UPD, SWP, GRAD> \
                 <<<dim3((unsigned)n), dim3(kThreads), kMrowLdsBytes, st>>>( \
-                tiles, n, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta)
+                tiles, n, c->reverse, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta)
             if (rc.V == 4) PG_MROW(4);
             else if (rc.V == 2) PG_MROW(2);
             else PG_MROW(1);
@@ -179,7 +182,7 @@ struct Launcher {
             constexpr int M = ((UPD && SWP) || GRAD || (RC > 8 && UPD)) ? 2 : 4;
             size_t lds = (size_t)RC * rc.max_seg * sizeof(float);
 #define PG_WIDE(VV) row_wide_kernel<VV, RC, M, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>( \
-                tiles, n, /*reverse=*/0, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta)
+                tiles, n, c->reverse, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta)
             if (rc.V == 4) PG_WIDE(4);
             else if (rc.V == 2) PG_WIDE(2);
             else PG_WIDE(1);
@@ -205,12 +208,14 @@ struct Launcher {
             row_launch<RC, false, true>(rc);
         }
     }
-    // One pass of the row-owner kernels over every parameter, front to back: sweep, update, or
+    // One pass of the row-owner kernels over every parameter: sweep, update, or
     // both; `grad` = update with the gradient term (X -= eta * G) in the same pass.
     void rows(bool upd, bool swp, bool grad = false) {
         if (status) return;
         int kind = grad ? K_UPDATE_SGD : (upd ? (swp ? K_UPDATE_SWEEP_P : K_UPDATE) : K_SWEEP_P);
-        for (const RowClass &rc : c->plan.row_classes) {
+        const auto &classes = c->plan.row_classes;
+        for (size_t k = 0; k < classes.size(); ++k) {
+            const RowClass &rc = classes[c->reverse ? classes.size() - 1 - k : k];
             if (rc.tiles.empty()) continue;
             begin(kind, rc.elems * 4.0 * (grad ? 3.0 : (upd ? 2.0 : 1.0)));
             switch (rc.RC) {
@@ -223,6 +228,11 @@ struct Launcher {
             check();
             end();
         }
+        turn();
+    }
+    // The next pass walks the parameters the other way.
+    void turn() {
+        if (c->alternate) c->reverse ^= 1;
     }
     // Workers without edges: their whole step is X -= eta * G.
     void sgd_isolated() {
@@ -235,8 +245,6 @@ struct Launcher {
         end();
     }
 
-    // The Q-sweep walks the parameters back to front: it starts on what the pass before it
-    // (always a front-to-back row pass) touched last.
     template <int RC>
     void col_launch(const ColClass &cc) {
         constexpr int U = (RC <= 2) ? 8 : 4;  // rows in flight per lane
@@ -245,13 +253,13 @@ struct Launcher {
         size_t lds = std::max((size_t)(cc.max_rows + 1) * RC * sizeof(float),
                               (size_t)(kThreads / 64 - 1) * 64 * 4 * sizeof(double));
 #define PG_COL(VV) col_kernel<VV, RC, U><<<dim3((unsigned)n), dim3(kThreads), lds, st>>>( \
-            c->d_col_tiles + cc.dev_first, n, /*reverse=*/c->col_reverse, c->d_pairs, c->d_cols, \
+            c->d_col_tiles + cc.dev_first, n, c->reverse, c->d_pairs, c->d_cols, \
             c->d_xs, left(), qw())
         if constexpr (RC < kWideCols) {
             PG_COL(0);
         } else if (c->plan.mfma_cols) {
 #define PG_MCOL(VV) mcol_kernel<VV, kMfmaColPrefetch><<<dim3((unsigned)n), dim3(kThreads), 0, st>>>( \
-            c->d_col_tiles + cc.dev_first, n, /*reverse=*/c->col_reverse, c->d_pairs, c->d_cols, \
+            c->d_col_tiles + cc.dev_first, n, c->reverse, c->d_pairs, c->d_cols, \
             c->d_xs, left(), qw())
             if (cc.V == 4) PG_MCOL(4);
             else if (cc.V == 2) PG_MCOL(2);
@@ -264,11 +272,11 @@ struct Launcher {
         }
 #undef PG_COL
     }
-    // The Q-sweep walks the parameters back to front: it starts on what the pass before it
-    // (always a front-to-back row pass) touched last.
     void sweep_q() {
         if (status) return;
-        for (const ColClass &cc : c->plan.col_classes) {
+        const auto &classes = c->plan.col_classes;
+        for (size_t k = 0; k < classes.size(); ++k) {
+            const ColClass &cc = classes[c->reverse ? classes.size() - 1 - k : k];
             if (cc.tiles.empty()) continue;
             begin(K_SWEEP_Q, cc.elems * 4.0);
             switch (cc.RC) {
@@ -281,6 +289,7 @@ struct Launcher {
             check();
             end();
         }
+        turn();
     }
     template <int NT, int RMAX>
     void orth_launch() {
@@ -425,7 +434,7 @@ int pg_init(pg_ctx **out, int n_workers, int n_edges, const int32_t *edges, cons
     if (!c) return PG_ERR_NOMEM;
     Tuning tune;
     if (const char *e = getenv("PG_ROW_TILE_BYTES")) tune.row_tile_bytes = std::max(1024, atoi(e));
-    if (const char *e = getenv("PG_COL_REVERSE")) c->col_reverse = atoi(e) != 0;
+    if (const char *e = getenv("PG_ALTERNATE")) c->alternate = atoi(e) != 0;
     if (const char *e = getenv("PG_COL_TILE_BYTES")) tune.col_tile_bytes = std::max(1024, atoi(e));
     if (const char *e = getenv("PG_WIDE_TILE_BYTES")) tune.wide_tile_bytes = std::max(1024, atoi(e));
     if (const char *e = getenv("PG_MFMA_ROWS")) tune.mfma_rows = atoi(e) != 0;

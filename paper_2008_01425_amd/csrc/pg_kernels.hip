@@ -570,12 +570,12 @@ struct BoolTag {
 // Two work-groups per CU: left alone the compiler takes every register it can (one work-group).
 template <int V, int RCM, int MB, int D, bool UPDATE, bool SWEEP, bool GRAD>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
-mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, const PairDesc *__restrict__ pairs,
+mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse, const PairDesc *__restrict__ pairs,
             const ColDesc *__restrict__ cols, float *const *__restrict__ xs,
             const float *__restrict__ qstate, const float *__restrict__ phat,
             double *__restrict__ pw, const float *const *__restrict__ gs, double eta) {
     extern __shared__ double smem[];
-    const RowTile t = tiles[blockIdx.x];
+    const RowTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
     const PairDesc pd = pairs[t.pair];
     float *X = xs[pd.worker] + pd.x_off;
     const float *Gp = GRAD ? gs[pd.worker] + pd.x_off : nullptr;

@@ -25,9 +25,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # device copy of known size (factors 2.000 and 1.000); see profiles/vgg16_r1_traffic_counters.txt.
 MEASURED_TRAFFIC_BYTES = {
     ("vgg16_r1", "update_sweep_p"): 960.2e6 + 943.6e6,
-    ("vgg16_r1", "update"): 963.8e6 + 941.8e6,
-    ("vgg16_r1", "update_sgd"): 1903.2e6 + 941.8e6,
-    ("vgg16_r1", "sweep_p"): 958.8e6 + 1.7e6,
+    ("vgg16_r1", "update"): 962.4e6 + 941.8e6,
+    ("vgg16_r1", "update_sgd"): 1902.9e6 + 941.8e6,
+    ("vgg16_r1", "sweep_p"): 957.5e6 + 1.8e6,
     ("vgg16_r1", "sweep_q"): 945.9e6 + 8.7e6,
 }
 

@@ -13,7 +13,7 @@
  *   - the workers form an undirected graph with a symmetric mixing weight w_e = W_ab on
  *     each edge e = (a, b) (assumption A4); each edge and matrix owns a projection state
  *     Q_e^l in R^{q_l x r_l}, r_l = min(rank, p_l, q_l), initialised by the CALLER with
- *     N(0, 1) entries (Algorithm 2, line 1);
+ *     N(0, 1) entries (initialisation of Algorithm 2);
  *   - with D_e = X_a - X_b taken at the start of the round, repeated `power_steps` times on
  *     the unchanged parameters:
  *         P_e    = X_a Q_e - X_b Q_e              (the products are formed per worker and
@@ -153,7 +153,7 @@ int pg_round(pg_ctx *ctx, float *const *worker_params, float *q_state, void *wor
              void *hip_stream);
 
 /*
- * One step of decentralized SGD with edge-wise compression (Algorithm 1, line 6):
+ * One step of decentralized SGD with edge-wise compression (the update step of Algorithm 1):
  *     X_i <- X_i + sum_j W_ij C(X_j - X_i) - eta * G_i
  * i.e. pg_round with the stochastic-gradient term folded into the update pass (the update then
  * reads X and G and writes X once: 12 instead of 8 + 12 bytes per parameter for a separate
@@ -171,7 +171,7 @@ int pg_round_sgd(pg_ctx *ctx, float *const *worker_params, const float *const *w
  * Algorithm 2 taken literally, one mat-vec iteration at a time.  `iterations` iterations,
  * numbered k_done + 1 ... k_done + iterations, run on the unchanged parameters and the
  * approximation of the LAST one is applied (the procedure overwrites its approximation in the
- * loop and returns it once); with `worker_grads` the step is line 6 of Algorithm 1.
+ * loop and returns it once); with `worker_grads` the step is the update step of Algorithm 1.
  *   odd k : vhat = v / |v| in R^q;  p  = X_a vhat - X_b vhat;      approximation p vhat^T;   v <- p
  *   even k: vhat = v / |v| in R^p;  p' = X_a^T vhat - X_b^T vhat;  approximation vhat p'^T;  v <- p'
  * The vector alternates between the two spaces: in R^q it lives in q_state (layout above), in

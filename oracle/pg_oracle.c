@@ -103,7 +103,7 @@ static void mat_t_vec(const real_t *X, int p, int q, const real_t *u, double *y)
  *              step's r_l orthonormal columns of length p (column k at +k*p)
  *   degenerate NULL, or [n_edges * r_l] flags of the last step
  *   G, eta     NULL, or [n_workers] pointers to p*q stochastic gradients and the learning rate:
- *              line 6 of Algorithm 1, X_i <- X_i + sum_j W_ij C(X_j - X_i) - eta * G_i, the
+ *              the update step of Algorithm 1, X_i <- X_i + sum_j W_ij C(X_j - X_i) - eta * G_i, the
  *              gradient term added to the same single rounding as the gossip term
  */
 int pgo_round_layer_sgd(int n_workers, int n_edges, const int32_t *edges, const double *edge_w,

@@ -256,7 +256,7 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
 
 // One wavefront per tile; `reverse` walks the tile list backwards so that a pass can start on
 // the data the previous pass touched last (still resident in the memory-side cache).
-//   GRAD  : (with UPDATE) also subtract eta * G[row, c]: line 6 of Algorithm 1 in one pass.
+//   GRAD  : (with UPDATE) also subtract eta * G[row, c]: the update step of Algorithm 1 in one pass.
 template <int RC, int M, int D, bool UPDATE, bool SWEEP, bool GRAD>
 __global__ void __launch_bounds__(kRowThreads)
 row_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,

@@ -6,7 +6,7 @@ the paper trains (its ResNet-20 and LSTM parameter tables in the appendix
 "Network architectures") and the other model shapes this build is measured on;
 values follow the paper's setting of workers that start from a common point
 and drift apart: X_i = B + sigma * N(0, 1) with a shared base B ~ N(0, 1), and
-projection vectors initialised entry-wise N(0, 1) (Algorithm 2, line 1).
+projection vectors initialised entry-wise N(0, 1) (initialisation of Algorithm 2).
 
 Every (worker, layer), (layer) and (edge, layer) block has its own counter-based
 stream (numpy Philox keyed by (seed, tag, indices)), so any single block can be

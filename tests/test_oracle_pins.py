@@ -269,7 +269,7 @@ def test_compressor_is_linear_in_the_difference():
 
 # ------------------------------------------------ Algorithm 2: v_ij = -v_ji
 def test_reversing_an_edge_negates_its_state_and_leaves_parameters_alone():
-    """Algorithm 2, line 1 and the closing note: v_ij = -v_ji and C(X_j - X_i) = -C(X_i - X_j).
+    """Algorithm 2's initialisation and its closing note: v_ij = -v_ji and C(X_j - X_i) = -C(X_i - X_j).
     Seen from the other endpoint an edge has the negated difference and the negated vector:
     the same Phat, the negated Q', the same parameters.  Keeping the vector and negating only
     the difference negates Phat instead and leaves Q' alone."""
@@ -437,9 +437,9 @@ def test_random_left_projections_contract_at_the_rate_of_theorem_1():
     assert mean >= 1 - 6 * rho * delta        # sanity: a rank-1 step cannot contract like full gossip
 
 
-# ------------------------------------------------ Algorithm 1, line 6: the gradient term
+# ------------------------------------------------ Algorithm 1's update step: the gradient term
 def test_sgd_term_without_edges_is_plain_sgd():
-    """Algorithm 1, line 6 with no neighbours: X <- X - eta * G."""
+    """Algorithm 1's update step with no neighbours: X <- X - eta * G."""
     rng = np.random.default_rng(30)
     prob = make(3, np.zeros((0, 2), np.int32), np.zeros(0), [(5, 4), (3, 1)])
     X, Q = rand_state(prob, rng)
@@ -452,7 +452,7 @@ def test_sgd_term_without_edges_is_plain_sgd():
 
 
 def test_sgd_term_adds_to_the_gossip_term_and_moves_the_mean_by_the_mean_gradient():
-    """Algorithm 1, line 6 is one expression: gossip correction (from the start-of-round
+    """The update step of Algorithm 1 is one expression: gossip correction (from the start-of-round
     parameters) minus eta * G.  So the result is the gossip-only result minus eta * G, the
     projection state is unaffected by G, and the worker mean moves by -eta * mean(G) (Lemma 1
     plus the gradient term)."""

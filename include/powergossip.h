@@ -161,7 +161,7 @@ int pg_round(pg_ctx *ctx, float *const *worker_params, float *q_state, void *wor
  *   worker_grads   host array of n_workers DEVICE pointers, laid out like the parameter
  *                  buffers (pg_param_floats floats, same layer offsets), 16-byte aligned;
  *                  read only.  Cached like worker_params.
- *   eta            learning rate (finite)
+ *   eta            learning rate (finite, else PG_ERR_ARG)
  * Workers without edges get X_i -= eta * G_i.  Other arguments and errors as pg_round.
  */
 int pg_round_sgd(pg_ctx *ctx, float *const *worker_params, const float *const *worker_grads,

@@ -10,7 +10,7 @@
  *
  * What is computed, and where the paper defines it:
  *   - the model is a list of matrices X in R^{p x q}, each handled separately
- *     (Section 2: "each weight and bias is considered separately"; conv
+ *     (Section 2: every weight and every bias is its own matrix; conv
  *     weights are p = output channels, q = inputs x kernel size); the caller
  *     loops over layers;
  *   - compressed gossip, Eq. (2) (the unnumbered display after Eq. (1) in
@@ -40,7 +40,7 @@
  *
  * Orthogonalisation: modified Gram-Schmidt, columns left to right, unit
  * 2-norm, no sign changes.  A column whose residual has squared norm below
- * max(DBL_MIN-scaled floor, 1e-10 * original squared norm) is "degenerate":
+ * max(FLT_MIN, 1e-10 * its squared norm before projection) is "degenerate":
  * its Phat column is zero, it contributes nothing to the update (Section 3.1:
  * a zero difference gives a zero update) and its Q column is left as it was.
  *
@@ -79,7 +79,7 @@ static void mat_vec(const real_t *X, int p, int q, const real_t *v, double *y)
     }
 }
 
-/* y[c] = sum_row X[row, c] * u[row] (Algorithm 2, even iteration: "the same, with X transposed"). */
+/* y[c] = sum_row X[row, c] * u[row] (Algorithm 2, even iteration: the product with X transposed). */
 static void mat_t_vec(const real_t *X, int p, int q, const real_t *u, double *y)
 {
     for (int c = 0; c < q; ++c)

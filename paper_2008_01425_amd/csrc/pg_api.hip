@@ -1,6 +1,7 @@
 // C ABI of the PowerGossip library: context life cycle, layout queries, launch sequencing.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -33,6 +34,7 @@ struct ProfRec {
 struct pg_ctx {
     Plan plan;
     bool uploaded = false;
+    bool touched_device = false;  // some HIP allocation was attempted: pg_destroy has things to free
     PairDesc *d_pairs = nullptr;
     ColDesc *d_cols = nullptr;
     RowTile *d_row_tiles = nullptr;
@@ -77,6 +79,7 @@ int upload_vec(T **dst, const std::vector<T> &src) {
 
 int do_upload(pg_ctx *c) {
     if (c->uploaded) return PG_OK;
+    c->touched_device = true;
     Plan &P = c->plan;
     std::vector<RowTile> rt;
     for (auto &rc : P.row_classes) {
@@ -459,7 +462,7 @@ int pg_init(pg_ctx **out, int n_workers, int n_edges, const int32_t *edges, cons
 
 int pg_destroy(pg_ctx *c) {
     if (!c) return PG_ERR_ARG;
-    if (c->uploaded) {
+    if (c->touched_device) {  // also after an upload that failed half way: free what it got
         (void)hipDeviceSynchronize();
         for (auto &r : c->recs) {
             (void)hipEventDestroy(r.t0);
@@ -530,7 +533,7 @@ int pg_round_sgd(pg_ctx *c, float *const *worker_params, const float *const *wor
     hipStream_t st = (hipStream_t)hip_stream;
     int rc = prepare(c, worker_params, q_state, workspace, st);
     if (rc) return rc;
-    if (!(eta == eta)) return PG_ERR_ARG;
+    if (!std::isfinite(eta)) return PG_ERR_ARG;
     if ((rc = prepare_grads(c, worker_grads, st))) return rc;
     Launcher L{c, st, q_state, (char *)workspace};
     L.eta = (double)eta;
@@ -554,7 +557,7 @@ int pg_iterate(pg_ctx *c, float *const *worker_params, float *q_state, float *p_
     hipStream_t st = (hipStream_t)hip_stream;
     int rc = prepare(c, worker_params, q_state, workspace, st);
     if (rc) return rc;
-    if (k_done < 0 || iterations < 1 || !(eta == eta)) return PG_ERR_ARG;
+    if (k_done < 0 || iterations < 1 || (worker_grads && !std::isfinite(eta))) return PG_ERR_ARG;
     if (c->plan.pstate_floats > 0 && (!p_state || ((uintptr_t)p_state & 15))) return PG_ERR_ARG;
     if (c->plan.max_layer_rank > 8) return PG_ERR_ARG;
     if (worker_grads && (rc = prepare_grads(c, worker_grads, st))) return rc;

@@ -85,6 +85,16 @@ class GossipBuffers:
             for e in range(self.n_edges):
                 self.set_q(e, l, wl.q_init(e, l))
 
+    def fill_from_arrays(self, X, Q, layers: Optional[Sequence[int]] = None):
+        """Fill from host arrays X[i][j] (p, q) and Q[e][j] (r, q) holding the listed layers
+        (default: all, in order)."""
+        ls = list(range(self.L)) if layers is None else list(layers)
+        for j, l in enumerate(ls):
+            for i in range(self.n):
+                self.set_layer(i, l, X[i][j])
+            for e in range(self.n_edges):
+                self.set_q(e, l, Q[e][j])
+
     # ---- the two entry points -------------------------------------------
     def round(self, stream: Optional[torch.cuda.Stream] = None):
         s = torch.cuda.current_stream(self.device) if stream is None else stream

@@ -104,6 +104,12 @@ class Workload:
     sigma: float               # std of the per-worker deviation from the base
     rounds: int                # rounds the configuration asks for in long parity runs
     seed: int = 0
+    # Optional planted spectrum (sigma_1, sigma_2, ...): every layer gets shared orthonormal
+    # directions u_k, v_k and worker i adds (i + 1) * sum_k sigma_k u_k v_k^T, so the difference
+    # of workers a and b is (a - b) * sum_k sigma_k u_k v_k^T + noise: singular values in the
+    # planted ratios on every edge (the paper's premise: differences with a fast-decaying
+    # spectrum, Section 3.1 and the appendix on power spectra), above a flat noise floor.
+    spectrum: Tuple[float, ...] = ()
 
     @property
     def n_edges(self) -> int:
@@ -131,7 +137,19 @@ class Workload:
         p, q = self.shapes[l]
         b = self.base(l) if base is None else base
         noise = self._rng(2, i, l).standard_normal((p, q), dtype=np.float32)
-        return (b + np.float32(self.sigma) * noise).astype(np.float32)
+        x = b + np.float32(self.sigma) * noise
+        if self.spectrum:
+            x = x.astype(np.float64) + (i + 1) * self.planted(l)
+        return x.astype(np.float32)
+
+    def planted(self, l: int) -> np.ndarray:
+        """sum_k sigma_k u_k v_k^T (float64) with random orthonormal u_k in R^p, v_k in R^q."""
+        p, q = self.shapes[l]
+        k = min(len(self.spectrum), p, q)
+        rng = self._rng(4, l)
+        u, _ = np.linalg.qr(rng.standard_normal((p, k)))
+        v, _ = np.linalg.qr(rng.standard_normal((q, k)))
+        return (u * np.asarray(self.spectrum[:k], dtype=np.float64)) @ v.T
 
     def q_init(self, e: int, l: int) -> np.ndarray:
         """Initial projection vectors of edge e, layer l: (r_l, q_l) float32, entry-wise N(0,1)."""

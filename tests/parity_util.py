@@ -1,5 +1,9 @@
 """Shared helpers of the GPU parity tests: run the HIP path and the CPU oracle on the same
 seeded inputs and compare element by element."""
+import copy
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 from oracle import pg_oracle as O
@@ -23,8 +27,9 @@ def oracle_problem(wl):
                      wl.rank, wl.power_steps)
 
 
-def compare_state(gb, X, Q, layers, tol, what="", phat=None, check_q=True):
-    """gb: GossipBuffers after its rounds; X[i][j], Q[e][j]: oracle state for layers[j]."""
+def compare_state(gb, X, Q, layers, tol, what="", phat=None, check_q=True, flags=None):
+    """gb: GossipBuffers after its rounds; X[i][j], Q[e][j]: oracle state for layers[j];
+    phat[e][j] / flags[j] (E, r_l): the oracle's last orthonormal columns and dropped flags."""
     worst = dict(x=0.0, q=0.0, ph=0.0)
     for j, l in enumerate(layers):
         for i in range(gb.n):
@@ -41,15 +46,57 @@ def compare_state(gb, X, Q, layers, tol, what="", phat=None, check_q=True):
                 e_ = rel_err(gb.get_phat(e, l), phat[e][j])
                 worst["ph"] = max(worst["ph"], e_)
                 assert e_ <= tol, f"{what}: Phat edge {e} layer {l}: rel err {e_:.3e} > {tol}"
+        if flags is not None:
+            for e in range(gb.n_edges):
+                assert np.array_equal(gb.get_flags(e, l), flags[j][e]), f"{what}: flags edge {e} layer {l}"
     return worst
 
 
-def oracle_rounds(wl, X, Q, rounds, layers):
-    """Run `rounds` oracle rounds in place on X[i][j] / Q[e][j] holding only `layers`."""
+class Snapshot:
+    """Oracle state after some round: X[i][j], Q[e][j], phat[e][j], degenerate[j] (E, r_l)."""
+
+    def __init__(self, X, Q, phat, degenerate):
+        self.X, self.Q, self.phat, self.degenerate = X, Q, phat, degenerate
+
+
+def oracle_rounds(wl, X, Q, rounds, layers, snap_at=()):
+    """Run `rounds` oracle rounds in place on X[i][j] / Q[e][j] holding only `layers`.
+
+    The oracle itself is single-threaded and handles one matrix per call; matrices are
+    independent (Section 2), so the loop over layers is spread over host threads here (the C
+    calls release the interpreter lock): every layer sees exactly the calls it would see in a
+    serial loop, so the results are bit-identical to one thread.  Returns the RoundInfo of the
+    last round; with `snap_at` (round numbers) also {round: Snapshot} of deep copies."""
     prob = oracle_problem(wl)
     sub = O.Problem(prob.n_workers, prob.edges, prob.edge_w, [prob.shapes[l] for l in layers],
                     prob.rank, prob.power_steps)
-    info = None
-    for _ in range(rounds):
-        info = O.gossip_round(sub, X, Q, want_phat=True)
-    return info
+    nL, E, n = len(layers), sub.n_edges, sub.n_workers
+    snaps = {t: [None] * nL for t in snap_at}
+    last = [None] * nL
+    O._lib("f32" if X[0][0].dtype == np.float32 else "f64")   # built and loaded before the threads start
+
+    def one_layer(j):
+        X_l = [X[i][j] for i in range(n)]
+        Q_l = [Q[e][j] for e in range(E)]
+        for t in range(1, rounds + 1):
+            ph, deg = O.round_layer(sub, j, X_l, Q_l, want_phat=True)
+            if t in snaps:
+                snaps[t][j] = ([a.copy() for a in X_l], [a.copy() for a in Q_l], copy.deepcopy(ph), deg.copy())
+            last[j] = (ph, deg)
+
+    order = sorted(range(nL), key=lambda j: -sub.shapes[j][0] * sub.shapes[j][1])
+    nthreads = max(1, min(16, os.cpu_count() or 1, nL))
+    with ThreadPoolExecutor(nthreads) as pool:
+        list(pool.map(one_layer, order))
+    info = O.RoundInfo()
+    info.phat = [[last[j][0][e] for j in range(nL)] for e in range(E)]
+    info.degenerate = [last[j][1] for j in range(nL)]
+    if not snap_at:
+        return info
+    out = {}
+    for t, per in snaps.items():
+        out[t] = Snapshot([[per[j][0][i] for j in range(nL)] for i in range(n)],
+                          [[per[j][1][e] for j in range(nL)] for e in range(E)],
+                          [[per[j][2][e] for j in range(nL)] for e in range(E)],
+                          [per[j][3] for j in range(nL)])
+    return info, out

@@ -199,3 +199,37 @@ def test_planner_tiles_cover_every_matrix_exactly_once(tmp_path):
     run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
     assert run.returncode == 0, run.stdout[-3000:]
     assert run.stdout.count("ok ") == 21 and "FAIL" not in run.stdout
+
+
+SAN = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-g"]
+
+
+def _run_sanitized(cmd, exe):
+    import subprocess
+    build = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+    assert build.returncode == 0, build.stderr[-3000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    env.pop("LD_PRELOAD", None)      # the sanitizer runtime must come first in the link order
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=600, env=env)
+    assert run.returncode == 0, (run.stdout[-2000:], run.stderr[-3000:])
+    assert "runtime error" not in run.stderr and "AddressSanitizer" not in run.stderr
+    return run.stdout
+
+
+def test_planner_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The host planner (every table the kernels index with) built with ASan + UBSan and run over
+    the same problems as the cover check: no out-of-bounds write, overflow or leak."""
+    exe = str(tmp_path / "plan_cover_san")
+    src = [os.path.join(ROOT, "tests", "plan_cover.cpp"),
+           os.path.join(ROOT, "paper_2008_01425_amd", "csrc", "pg_plan.cpp")]
+    out = _run_sanitized(["g++", "-O1", "-std=c++17"] + SAN + ["-o", exe] + src, exe)
+    assert "FAIL" not in out and out.count("ok ") == 21
+
+
+@pytest.mark.parametrize("define", [[], ["-DPGO_ALL_DOUBLE"]])
+def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path, define):
+    """Both builds of the CPU oracle, all three entry points, on odd little problems."""
+    exe = str(tmp_path / "oracle_san")
+    src = os.path.join(ROOT, "tests", "oracle_sanitize.c")
+    out = _run_sanitized(["gcc", "-O1", "-std=c11", "-ffp-contract=off"] + SAN + define + ["-o", exe, src, "-lm"], exe)
+    assert "oracle sanitize ok" in out

@@ -396,13 +396,13 @@ def test_vector_lengths_reproduce_the_printed_compression_ratios():
             if l.strip() and not l.startswith("#")]
     rng = np.random.default_rng(15)
     for p, q, printed in [(int(a), int(b), int(c)) for a, b, c in rows]:
-        if p * q <= 64 * 576:       # run the oracle on the small ones to read its vector lengths
-            prob = make(2, [[0, 1]], 0.5, [(p, q)])
-            X, Q = rand_state(prob, rng)
-            info = O.gossip_round(prob, X, Q, want_phat=True)
-            sent_odd, sent_even = info.phat[0][0].size, Q[0][0].size
-        else:
-            sent_odd, sent_even = p, q
+        # run the oracle on every printed shape (float storage for the two LSTM matrices) and
+        # read the lengths of the vectors it produces
+        prob = make(2, [[0, 1]], 0.5, [(p, q)])
+        X, Q = rand_state(prob, rng, np.float32 if p * q > 64 * 576 else np.float64)
+        info = O.gossip_round(prob, X, Q, want_phat=True)
+        sent_odd, sent_even = info.phat[0][0].size, Q[0][0].size
+        assert (sent_odd, sent_even) == (p, q)
         assert round(p * q / ((sent_odd + sent_even) / 2)) == printed
 
 
@@ -591,3 +591,99 @@ def test_iterated_single_steps_reach_the_top_singular_pair():
     assert np.allclose(Vp[0][0][0], s1 * ss[0] * Us[:, 0], atol=1e-8)
     s2 = np.sign(Vq[0][0][0] @ Vts[0])
     assert np.allclose(Vq[0][0][0], s2 * ss[0] * Vts[0], atol=1e-8)
+
+
+def test_iteration_on_identical_workers_writes_a_zero_vector_then_drops_it_and_keeps_the_other_buffer():
+    """Section 3.1: a zero difference gives a zero update.  Algorithm 2 on identical workers: the
+    odd iteration stores p_j - p_i = 0 in the R^p buffer; the next (even) iteration cannot
+    normalise that vector, so it is dropped: nothing is applied, and the R^q buffer it would have
+    written keeps its bits (zeros there would be a state that can never recover)."""
+    rng = np.random.default_rng(45)
+    n, p, q = 3, 7, 5
+    prob = make(n, ring(n), 1 / 3, [(p, q)], rank=2)
+    base = rng.standard_normal((p, q))
+    X = [[base.copy()] for _ in range(n)]
+    Vq, Vp = _alg2_state(prob, rng)
+    for e in range(n):
+        Vp[e][0][:] = rng.standard_normal((2, p))       # stale content that the odd iteration must overwrite
+    vq0 = [Vq[e][0].copy() for e in range(n)]
+    flags = O.alg2_round(prob, X, Vq, Vp, 0, 1)          # k = 1, odd
+    assert not flags[0].any()                            # a random v normalises fine
+    for e in range(n):
+        assert not Vp[e][0].any()                        # p_j - p_i = 0, written
+        assert np.array_equal(Vq[e][0], vq0[e])
+    flags = O.alg2_round(prob, X, Vq, Vp, 1, 1)          # k = 2, even: v = 0 in R^p
+    assert flags[0].all()
+    for e in range(n):
+        assert np.array_equal(Vq[e][0], vq0[e])          # untouched, bit for bit
+        assert not Vp[e][0].any()
+    for i in range(n):
+        assert np.array_equal(X[i][0], base)
+    # and the state recovers once the workers differ again
+    X[0][0] += rng.standard_normal((p, q))
+    flags = O.alg2_round(prob, X, Vq, Vp, 2, 1)          # k = 3, odd, from the kept R^q vectors
+    assert not flags[0].any() and Vp[0][0].any()
+
+
+def test_iterations_on_a_rank_one_difference_drop_the_second_column_in_the_even_iteration():
+    """Algorithm 2 at rank 2 on D = u v^T (reading: Gram-Schmidt over the stored columns, a column
+    that cannot be normalised contributes nothing and leaves the buffer it would have written
+    alone).  Odd iteration: both unit vectors are fine, both products are multiples of u.  Even
+    iteration: the second stored column is parallel to the first, its residual vanishes, it is
+    dropped; the first column alone gives uhat (D^T uhat)^T = D, so with w = 1/2 both workers
+    land on their mean, and column 2 of the R^q buffer keeps its bits."""
+    rng = np.random.default_rng(46)
+    p, q = 9, 6
+    u, v = rng.standard_normal(p), rng.standard_normal(q)
+    base = rng.standard_normal((p, q))
+    prob = make(2, [[0, 1]], 0.5, [(p, q)], rank=2)
+    X = [[base + np.outer(u, v)], [base.copy()]]
+    Vq, Vp = _alg2_state(prob, rng)
+    vq0 = Vq[0][0].copy()
+    flags = O.alg2_round(prob, X, Vq, Vp, 0, 2)          # k = 1 (odd) and k = 2 (even), one call
+    assert flags[0].tolist() == [[0, 1]]
+    uh = u / np.linalg.norm(u)
+    s = np.sign(Vp[0][0][0] @ uh)
+    # R^p buffer after the odd iteration: D vhat_k = u (v . vhat_k), both columns along u
+    for k in range(2):
+        assert np.allclose(np.abs(Vp[0][0][k] @ uh), np.linalg.norm(Vp[0][0][k]), rtol=1e-12)
+    assert np.allclose(Vq[0][0][0], s * np.linalg.norm(u) * v, atol=1e-12)   # D^T uhat
+    assert np.array_equal(Vq[0][0][1], vq0[1])                               # dropped: kept
+    mean = base + 0.5 * np.outer(u, v)
+    assert np.allclose(X[0][0], mean, atol=1e-12) and np.allclose(X[1][0], mean, atol=1e-12)
+
+
+def test_gradient_term_of_algorithm_1_inside_the_single_iteration_procedure():
+    """The update step of Algorithm 1 around Algorithm 2's compressor: without neighbours the step
+    is X - eta G; with neighbours it is the gradient-free result minus eta G, for an odd and for
+    an even last iteration, and neither vector buffer depends on G."""
+    rng = np.random.default_rng(47)
+    lone = make(3, np.zeros((0, 2), np.int32), np.zeros(0), [(5, 4), (3, 1)])
+    X, _ = rand_state(lone, rng)
+    G = [[rng.standard_normal(a.shape) for a in row] for row in X]
+    X0 = [[a.copy() for a in row] for row in X]
+    O.alg2_round(lone, X, [], [], 0, 1, G=G, eta=0.2)
+    for i in range(3):
+        for l in range(2):
+            assert np.allclose(X[i][l], X0[i][l] - 0.2 * G[i][l], atol=1e-15)
+            assert not np.array_equal(X[i][l], X0[i][l])
+    n = 5
+    prob = make(n, ring(n), 1 / 3, [(7, 6), (4, 1)], rank=2)
+    for k_done, its in ((0, 1), (1, 1), (0, 2), (2, 3)):
+        X, _ = rand_state(prob, rng)
+        Vq, Vp = _alg2_state(prob, rng)
+        for e in range(n):
+            for l in range(2):
+                Vp[e][l][:] = rng.standard_normal(Vp[e][l].shape)
+        G = [[rng.standard_normal(a.shape) for a in row] for row in X]
+        Xp = [[a.copy() for a in row] for row in X]
+        Vqp = [[a.copy() for a in row] for row in Vq]
+        Vpp = [[a.copy() for a in row] for row in Vp]
+        O.alg2_round(prob, X, Vq, Vp, k_done, its, G=G, eta=0.05)
+        O.alg2_round(prob, Xp, Vqp, Vpp, k_done, its)
+        for l in range(2):
+            for i in range(n):
+                assert np.allclose(X[i][l], Xp[i][l] - 0.05 * G[i][l], atol=1e-14)
+                assert not np.allclose(X[i][l], Xp[i][l], atol=1e-6)
+            for e in range(n):
+                assert np.array_equal(Vq[e][l], Vqp[e][l]) and np.array_equal(Vp[e][l], Vpp[e][l])

@@ -83,6 +83,8 @@ def oracle_rounds(wl, X, Q, rounds, layers, snap_at=()):
             if t in snaps:
                 snaps[t][j] = ([a.copy() for a in X_l], [a.copy() for a in Q_l], copy.deepcopy(ph), deg.copy())
             last[j] = (ph, deg)
+            if sub.shapes[j][0] * sub.shapes[j][1] >= 10_000_000:   # a long serial call: say where it is
+                print(f"   oracle: layer {layers[j]} {sub.shapes[j]} round {t} of {rounds}", flush=True)
 
     order = sorted(range(nL), key=lambda j: -sub.shapes[j][0] * sub.shapes[j][1])
     nthreads = max(1, min(16, os.cpu_count() or 1, nL))

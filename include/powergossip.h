@@ -60,7 +60,8 @@ enum {
     PG_ERR_TOPOLOGY = -2, /* worker index out of range, self-loop, duplicate edge (either orientation) */
     PG_ERR_SHAPE = -3,    /* a layer with p < 1 or q < 1 */
     PG_ERR_NOMEM = -4,    /* host or device allocation failed */
-    PG_ERR_DEVICE = -5    /* a HIP call failed (no device, launch error, ...) */
+    PG_ERR_DEVICE = -5,   /* a HIP call failed (no device, launch error, ...) */
+    PG_ERR_TOO_LARGE = -6 /* pg_round_static: the problem needs more than PG_STATIC_WORKSPACE_BYTES */
 };
 
 /* Static, NUL-terminated description of a status code.  Never NULL. */
@@ -151,6 +152,23 @@ int pg_upload(pg_ctx *ctx);
  */
 int pg_round(pg_ctx *ctx, float *const *worker_params, float *q_state, void *workspace,
              void *hip_stream);
+
+/*
+ * pg_round for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same round, same results bit for bit, but the
+ * workspace is a fixed array of PG_STATIC_WORKSPACE_BYTES that lives inside the library's code
+ * object on every GPU it is loaded on (held until the process ends), and the call makes no
+ * hipMalloc, hipFree or other allocating call: no table upload (the context must have been
+ * through pg_upload, else PG_ERR_ARG), no timing events (pg_profile_enable is ignored).  A new
+ * set of worker_params pointers is still copied to the device table (a synchronous copy).
+ * A problem with pg_workspace_bytes > PG_STATIC_WORKSPACE_BYTES is refused with
+ * PG_ERR_TOO_LARGE and nothing is launched.  All contexts and calls on one GPU share the one
+ * array: calls that overlap on a GPU (different streams or threads) race; calls ordered on one
+ * stream, or separated by a synchronisation, do not.  Phat and the flags of the round are not
+ * reachable through pg_ws_*_offset for this call.  Other arguments and errors as pg_round.
+ */
+#define PG_STATIC_WORKSPACE_BYTES (32u << 20)
+int pg_round_static(pg_ctx *ctx, float *const *worker_params, float *q_state, void *hip_stream);
 
 /*
  * One step of decentralized SGD with edge-wise compression (the update step of Algorithm 1):

@@ -12,12 +12,13 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpowergossip.so")
 
-PG_OK, PG_ERR_ARG, PG_ERR_TOPOLOGY, PG_ERR_SHAPE, PG_ERR_NOMEM, PG_ERR_DEVICE = 0, -1, -2, -3, -4, -5
+PG_OK, PG_ERR_ARG, PG_ERR_TOPOLOGY, PG_ERR_SHAPE, PG_ERR_NOMEM, PG_ERR_DEVICE, PG_ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5, -6
+PG_STATIC_WORKSPACE_BYTES = 32 << 20
 
 EXPORTS = [
     "pg_strerror", "pg_init", "pg_destroy", "pg_param_floats", "pg_layer_offset", "pg_layer_rank",
     "pg_qstate_floats", "pg_q_offset", "pg_workspace_bytes", "pg_ws_phat_offset",
-    "pg_ws_flag_offset", "pg_message_floats", "pg_round_bytes", "pg_upload", "pg_round", "pg_round_sgd",
+    "pg_ws_flag_offset", "pg_message_floats", "pg_round_bytes", "pg_upload", "pg_round", "pg_round_static", "pg_round_sgd",
     "pg_run", "pg_iterate", "pg_pstate_floats", "pg_p_offset",
     "pg_profile_enable", "pg_profile_collect",
 ]
@@ -73,6 +74,8 @@ def _load():
     lib.pg_upload.argtypes = [vp]
     lib.pg_round.restype = ci
     lib.pg_round.argtypes = [vp, vp, vp, vp, vp]
+    lib.pg_round_static.restype = ci
+    lib.pg_round_static.argtypes = [vp, vp, vp, vp]
     lib.pg_round_sgd.restype = ci
     lib.pg_round_sgd.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp]
     lib.pg_pstate_floats.restype = sz
@@ -151,6 +154,11 @@ def _ptr_table(worker_ptrs: Sequence[int]):
 def pg_round(ctx, worker_ptrs: Sequence[int], q_ptr: int, ws_ptr: int, stream: int = 0) -> None:
     """worker_ptrs: device addresses of the n parameter buffers; q_ptr / ws_ptr: device addresses."""
     _check(lib.pg_round(ctx, _ptr_table(worker_ptrs), q_ptr, ws_ptr, stream))
+
+
+def pg_round_static(ctx, worker_ptrs: Sequence[int], q_ptr: int, stream: int = 0) -> None:
+    """pg_round on the library's static workspace: no allocation of any kind inside the call."""
+    _check(lib.pg_round_static(ctx, _ptr_table(worker_ptrs), q_ptr, stream))
 
 
 def pg_round_sgd(ctx, worker_ptrs: Sequence[int], grad_ptrs: Sequence[int], eta: float, q_ptr: int,

@@ -18,6 +18,15 @@ namespace {
 
 constexpr int kOrthThreads = 1024;
 
+// Workspace of pg_round_static: device memory that exists from the moment the library's code
+// object is loaded on a GPU (one copy per GPU, at its own address, held until the process
+// ends), so that a round can run without any allocation.  In host code this name is only a
+// handle for hipGetSymbolAddress; kernels and copies take the address that call returns.
+static __device__ __align__(256) unsigned char scratch[PG_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];  // per device: address of `scratch` there (null = not asked yet)
+
 enum Kind { K_SWEEP_P = 0, K_ORTH_P, K_SWEEP_Q, K_COMBINE_Q, K_UPDATE, K_UPDATE_SWEEP_P, K_UPDATE_SGD,
             K_ORTH_V, K_COMBINE_P, K_COUNT };
 const char *const kKindName[K_COUNT] = {"sweep_p", "orth_p", "sweep_q", "combine_q", "update",
@@ -77,6 +86,20 @@ int upload_vec(T **dst, const std::vector<T> &src) {
     return PG_OK;
 }
 
+// Address of the static workspace on the current device (asked once per device).
+int static_scratch(void **out) {
+    int dev = -1;
+    PG_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return PG_ERR_DEVICE;
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        PG_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PG_OK;
+}
+
 int do_upload(pg_ctx *c) {
     if (c->uploaded) return PG_OK;
     c->touched_device = true;
@@ -102,6 +125,8 @@ int do_upload(pg_ctx *c) {
     if ((rc = upload_vec(&c->d_iso, P.isolated_pairs))) return rc;
     PG_HIP(hipMalloc((void **)&c->d_xs, sizeof(float *) * (size_t)P.n));
     PG_HIP(hipMalloc((void **)&c->d_gs, sizeof(float *) * (size_t)P.n));
+    void *unused = nullptr;
+    if ((rc = static_scratch(&unused))) return rc;
     c->uploaded = true;
     return PG_OK;
 }
@@ -127,6 +152,7 @@ struct Launcher {
     // vectors (length p) the sweeps and the update read, when they are not the state / Phat
     const float *rhs = nullptr;
     const float *lhs = nullptr;
+    bool quiet = false;  // never record timing events (creating an event allocates)
     int status = PG_OK;
 
     const float *right() const { return rhs ? rhs : qstate; }
@@ -151,14 +177,14 @@ struct Launcher {
         return e;
     }
     void begin(int kind, double bytes) {
-        if (!c->profiling || status) return;
+        if (!c->profiling || quiet || status) return;
         ProfRec r{kind, bytes, get_event(), get_event()};
         if (status) return;
         if (hipEventRecord(r.t0, st) != hipSuccess) status = PG_ERR_DEVICE;
         c->recs.push_back(r);
     }
     void end() {
-        if (!c->profiling || status) return;
+        if (!c->profiling || quiet || status) return;
         if (hipEventRecord(c->recs.back().t1, st) != hipSuccess) status = PG_ERR_DEVICE;
     }
     void check() {
@@ -358,13 +384,15 @@ struct Launcher {
     }
 };
 
-int prepare(pg_ctx *c, float *const *worker_params, float *q_state, void *workspace, hipStream_t st) {
+int prepare(pg_ctx *c, float *const *worker_params, float *q_state, void *workspace, hipStream_t st,
+            bool may_allocate = true) {
     if (!c || !worker_params || !workspace) return PG_ERR_ARG;
     const Plan &P = c->plan;
     if (P.qstate_floats > 0 && !q_state) return PG_ERR_ARG;
     if (((uintptr_t)q_state & 15) || ((uintptr_t)workspace & 255)) return PG_ERR_ARG;
     for (int i = 0; i < P.n; ++i)
         if (!worker_params[i] || ((uintptr_t)worker_params[i] & 15)) return PG_ERR_ARG;
+    if (!c->uploaded && !may_allocate) return PG_ERR_ARG;
     int rc = do_upload(c);
     if (rc) return rc;
     bool same = c->xs_cached.size() == (size_t)P.n;
@@ -394,12 +422,13 @@ int prepare_grads(pg_ctx *c, const float *const *worker_grads, hipStream_t st) {
 }
 
 int run_rounds(pg_ctx *c, float *const *worker_params, float *q_state, void *workspace,
-               void *hip_stream, int rounds, bool fuse) {
+               void *hip_stream, int rounds, bool fuse, bool may_allocate = true) {
     hipStream_t st = (hipStream_t)hip_stream;
-    int rc = prepare(c, worker_params, q_state, workspace, st);
+    int rc = prepare(c, worker_params, q_state, workspace, st, may_allocate);
     if (rc) return rc;
     if (c->plan.n_edges == 0 || rounds == 0) return PG_OK;
     Launcher L{c, st, q_state, (char *)workspace};
+    L.quiet = !may_allocate;
     const int s = c->plan.steps;
     // Measured: with the passes that write (update + sweep) walking forwards and the Q-sweeps
     // backwards a run of fused rounds is 4 % faster than its mirror image, so a run starts forwards.
@@ -429,6 +458,7 @@ const char *pg_strerror(int status) {
         case PG_ERR_SHAPE: return "invalid layer shape";
         case PG_ERR_NOMEM: return "out of memory";
         case PG_ERR_DEVICE: return "HIP call failed";
+        case PG_ERR_TOO_LARGE: return "problem needs more workspace than the static one holds";
         default: return "unknown status";
     }
 }
@@ -526,6 +556,18 @@ int pg_upload(pg_ctx *c) {
 
 int pg_round(pg_ctx *c, float *const *worker_params, float *q_state, void *workspace, void *hip_stream) {
     return run_rounds(c, worker_params, q_state, workspace, hip_stream, 1, false);
+}
+
+int pg_round_static(pg_ctx *c, float *const *worker_params, float *q_state, void *hip_stream) {
+    if (!c) return PG_ERR_ARG;
+    if (!c->uploaded) return PG_ERR_ARG;  // uploading allocates: pg_upload comes first
+    if (c->plan.ws_bytes > (size_t)PG_STATIC_WORKSPACE_BYTES) return PG_ERR_TOO_LARGE;
+    void *ws = nullptr;
+    int rc = static_scratch(&ws);
+    if (rc) return rc;
+    // Nothing in the workspace has to start at zero: every section is written by the round's own
+    // kernels before it is read, so whatever an earlier call (of any context) left is harmless.
+    return run_rounds(c, worker_params, q_state, ws, hip_stream, 1, false, /*may_allocate=*/false);
 }
 
 int pg_round_sgd(pg_ctx *c, float *const *worker_params, const float *const *worker_grads, float eta,

@@ -100,6 +100,10 @@ class GossipBuffers:
         s = torch.cuda.current_stream(self.device) if stream is None else stream
         B.pg_round(self.ctx, self.ptrs, self.q.data_ptr(), self.ws.data_ptr(), s.cuda_stream)
 
+    def round_static(self, stream: Optional[torch.cuda.Stream] = None):
+        s = torch.cuda.current_stream(self.device) if stream is None else stream
+        B.pg_round_static(self.ctx, self.ptrs, self.q.data_ptr(), s.cuda_stream)
+
     def alloc_grads(self):
         """Gradient buffers laid out like the parameter buffers (zero-filled)."""
         self.g = [torch.zeros(self.N, dtype=torch.float32, device=self.device) for _ in range(self.n)]

@@ -30,8 +30,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_strerror_covers_all_codes():
-    texts = {B.pg_strerror(c) for c in (0, -1, -2, -3, -4, -5)}
-    assert len(texts) == 6 and all(texts)
+    texts = {B.pg_strerror(c) for c in (0, -1, -2, -3, -4, -5, -6)}
+    assert len(texts) == 7 and all(texts)
     assert "unknown" in B.pg_strerror(-99)
 
 
@@ -68,6 +68,12 @@ def test_bad_arguments_are_rejected():
     assert B.lib.pg_init(None, 1, 0, None, None, 1, None, None, 1, 1) == B.PG_ERR_ARG
     assert B.lib.pg_destroy(None) == B.PG_ERR_ARG
     assert B.lib.pg_round(None, None, None, None, None) == B.PG_ERR_ARG
+    assert B.lib.pg_round_static(None, None, None, None) == B.PG_ERR_ARG
+    # the static-workspace round never uploads (that allocates): a context that has not been
+    # through pg_upload is refused before any HIP call
+    ctx = _init(3, ok_edges, 0.2, [(4, 4)])
+    assert B.lib.pg_round_static(ctx, None, None, None) == B.PG_ERR_ARG
+    B.pg_destroy(ctx)
 
 
 def test_layouts_are_aligned_disjoint_and_complete():

@@ -1,0 +1,90 @@
+"""pg_round_static -- the round on the library's static workspace, for callers that cannot
+allocate -- against pg_round on the same inputs: two calls in a row, the second on a smaller
+problem (the shared workspace then still holds the first call's contents), then more rounds
+interleaved between the two contexts.  Bit for bit: both entry points run the same kernels."""
+import numpy as np
+import pytest
+
+from paper_2008_01425_amd import binding as B
+from paper_2008_01425_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(wl):
+    from paper_2008_01425_amd.device import GossipBuffers
+    X, Q = wl.all_params(), wl.all_q()
+    a, b = GossipBuffers.from_workload(wl, fill=False), GossipBuffers.from_workload(wl, fill=False)
+    a.fill_from_arrays(X, Q)
+    b.fill_from_arrays(X, Q)
+    return a, b
+
+
+def _same(a, b, what):
+    import torch
+    torch.cuda.synchronize()
+    for i in range(a.n):
+        assert np.array_equal(a.x[i].cpu().numpy(), b.x[i].cpu().numpy()), f"{what}: worker {i}"
+    assert np.array_equal(a.q.cpu().numpy(), b.q.cpu().numpy()), f"{what}: state"
+
+
+def test_static_workspace_round_matches_pg_round_twice_in_a_row_second_call_smaller():
+    import torch
+    big = W.get("vgg16_r2")        # 25.6 MiB of workspace: most of the static array
+    ew = np.full((5,), 1 / 3, np.float32)
+    small = W.Workload("small_ragged", 5, W.ring_edges(5), ew,
+                       [(37, 27), (130, 50), (9, 147), (700, 1), (5, 3), (64, 1028)], 2, 2, 0.05, 10, 3)
+    assert B.pg_workspace_bytes(B.pg_init(big.n_workers, big.edges, big.edge_w, [s[0] for s in big.shapes],
+                                          [s[1] for s in big.shapes], big.rank, big.power_steps)) \
+        <= B.PG_STATIC_WORKSPACE_BYTES
+    print("case static big", flush=True)
+    a1, b1 = _pair(big)
+    a2, b2 = _pair(small)
+    b1.round()                      # the existing entry point first: every kernel is loaded after this
+    b2.round()
+    torch.cuda.synchronize()
+    free_before = torch.cuda.mem_get_info()[0]
+    a1.round_static()               # first call
+    a2.round_static()               # second call, smaller input, same workspace
+    torch.cuda.synchronize()
+    assert torch.cuda.mem_get_info()[0] >= free_before, "device memory was allocated inside pg_round_static"
+    _same(a1, b1, "first call")
+    _same(a2, b2, "second, smaller call")
+    print("case static interleaved", flush=True)
+    for _ in range(2):
+        a2.round_static(); a1.round_static(); a2.round_static()
+        b2.round(); b1.round(); b2.round()
+    _same(a1, b1, "interleaved big")
+    _same(a2, b2, "interleaved small")
+    # against the oracle as well, to the one-round bar, on the small problem from fresh inputs
+    from parity_util import TOL_1, compare_state, oracle_rounds
+    a3, _b3 = _pair(small)
+    _b3.close()
+    a3.round_static()
+    X, Q = small.all_params(), small.all_q()
+    layers = list(range(len(small.shapes)))
+    oracle_rounds(small, X, Q, 1, layers)
+    compare_state(a3, X, Q, layers, TOL_1, what="static vs oracle")
+    for gb in (a1, b1, a2, b2, a3):
+        gb.close()
+
+
+def test_static_workspace_round_refuses_what_does_not_fit():
+    from paper_2008_01425_amd.device import GossipBuffers
+    wl = W.get("lstm")             # 264 MiB of workspace
+    ctx = B.pg_init(wl.n_workers, wl.edges, wl.edge_w, [s[0] for s in wl.shapes], [s[1] for s in wl.shapes],
+                    wl.rank, wl.power_steps)
+    assert B.pg_workspace_bytes(ctx) > B.PG_STATIC_WORKSPACE_BYTES
+    B.pg_upload(ctx)
+    with pytest.raises(B.PGError) as e:
+        B.pg_round_static(ctx, [256] * wl.n_workers, 256, 0)   # refused before any pointer is used
+    assert e.value.status == B.PG_ERR_TOO_LARGE
+    B.pg_destroy(ctx)
+    # a context that was never uploaded is refused too (uploading would allocate)
+    gb = GossipBuffers.from_workload(W.get("tiny"))
+    ctx = B.pg_init(4, W.ring_edges(4), np.full((4,), 1 / 3, np.float32), [64, 32, 16], [32, 16, 1], 1, 1)
+    with pytest.raises(B.PGError) as e:
+        B.pg_round_static(ctx, gb.ptrs, gb.q.data_ptr(), 0)
+    assert e.value.status == B.PG_ERR_ARG
+    B.pg_destroy(ctx)
+    gb.close()

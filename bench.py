@@ -3,15 +3,17 @@
 
 A "step" is one gossip round over the whole synthetic parameter set (every worker, every
 layer): power_steps x (P-sweep, orthonormalise, Q-sweep, combine) and the rank-r update.
-The timed region runs `--steps` rounds through pg_run (consecutive rounds, the update of one
-round sharing its pass with the first sweep of the next) with all inputs resident in HBM.
-Prints ONE JSON line.
+The timed region runs `--steps` rounds of the headline workload through pg_run (consecutive
+rounds, the update of one round sharing its pass with the first sweep of the next) with all
+inputs resident in HBM.  The other named configurations are measured after it (a few rounds
+each, HIP-event timed) and reported under "other_workloads".  Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -19,17 +21,24 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+TARGET_FRAC = 0.70     # of peak, for the two sweeps on the VGG-16-shaped ring
 
-# Bytes that crossed the L2 -> fabric boundary per launch of a kernel kind, from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs of this script, each scaled by the same counter's reading for a plain
-# device copy of known size (factors 2.000 and 1.000); see profiles/vgg16_r1_traffic_counters.txt.
-MEASURED_TRAFFIC_BYTES = {
-    ("vgg16_r1", "update_sweep_p"): 960.2e6 + 943.6e6,
-    ("vgg16_r1", "update"): 962.4e6 + 941.8e6,
-    ("vgg16_r1", "update_sgd"): 1902.9e6 + 941.8e6,
-    ("vgg16_r1", "sweep_p"): 957.5e6 + 1.8e6,
-    ("vgg16_r1", "sweep_q"): 945.9e6 + 8.7e6,
-}
+
+def traffic_from_profiles(workload: str):
+    """Bytes that crossed the L2 -> fabric boundary per launch of each kernel kind, as measured by
+    rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (scaled by the same counters'
+    reading for a plain copy of known size) and committed under profiles/.  Returns
+    ({kind: bytes}, file name) or ({}, None) when no summary of this workload is there."""
+    rel = os.path.join("profiles", f"{workload}_traffic_counters.txt")
+    path = os.path.join(ROOT, rel)
+    out = {}
+    if not os.path.exists(path):
+        return out, None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 5 and f[0] == "traffic":      # traffic <kind> <read B> <written B> <total B>
+            out[f[1]] = float(f[4])
+    return out, rel
 
 
 def cpu_baseline(wl, seconds_budget: float):
@@ -53,18 +62,98 @@ def cpu_baseline(wl, seconds_budget: float):
                       f"{dt:.1f} s on one host core ({os.cpu_count()} visible)"}
 
 
+def event_times(fn, reps: int, per_call: int):
+    """ms per round of `reps` calls of fn (each `per_call` rounds), timed with HIP events on the
+    stream the library launches on (torch's current stream)."""
+    import torch
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    evs[0].record()
+    for r in range(reps):
+        fn()
+        evs[r + 1].record()
+    torch.cuda.synchronize()
+    ms = [evs[r].elapsed_time(evs[r + 1]) / per_call for r in range(reps)]
+    return {"median": statistics.median(ms), "min": min(ms), "max": max(ms), "samples": reps,
+            "rounds_per_sample": per_call}
+
+
+def kernel_table(B, gb, fn):
+    """Per-kernel-kind durations of whatever fn launches: HIP events around every launch."""
+    import torch
+    B.pg_profile_enable(gb.ctx, True)
+    fn()
+    torch.cuda.synchronize()
+    rows = B.pg_profile_collect(gb.ctx)
+    B.pg_profile_enable(gb.ctx, False)
+    out = {}
+    for r in rows:
+        gbs = r["bytes"] / (r["ms"] * 1e-3) / 1e9 if r["ms"] > 0 else 0.0
+        out[r["name"]] = {"launches": r["launches"], "avg_ms": r["ms"] / max(1, r["launches"]),
+                          "total_ms": r["ms"],
+                          "algorithmic_bytes_per_launch": r["bytes"] / max(1, r["launches"]),
+                          "GBps": gbs, "frac_of_peak": gbs / HBM_PEAK_GBS}
+    return out
+
+
+def measure_other(name: str, rounds: int):
+    """A named configuration beside the headline: ms per round through pg_run and pg_round
+    (HIP events), per-kernel GB/s in both pipelines, bytes per parameter per round."""
+    import torch
+    from paper_2008_01425_amd import binding as B
+    from paper_2008_01425_amd import workloads as W
+    from paper_2008_01425_amd.device import GossipBuffers
+    wl = W.get(name)
+    gb = GossipBuffers.from_workload(wl)
+    gb.run(3)
+    torch.cuda.synchronize()
+    reps = 5
+    t_run = event_times(lambda: gb.run(rounds), reps, rounds)
+    gb.round()
+    t_round = event_times(lambda: gb.round(), max(reps, rounds), 1)
+    kp = min(rounds, 10)
+    k_fused = kernel_table(B, gb, lambda: gb.run(kp))
+    k_unfused = kernel_table(B, gb, lambda: [gb.round() for _ in range(kp)])
+    nparam = wl.n_workers * wl.params_per_worker
+    bf, bu = B.pg_round_bytes(gb.ctx, True), B.pg_round_bytes(gb.ctx, False)
+    traffic, src = traffic_from_profiles(name)
+    slim = lambda tab: {k: {"avg_ms": v["avg_ms"], "GBps": v["GBps"], "frac_of_peak": v["frac_of_peak"],
+                            "launches": v["launches"]} for k, v in tab.items()}
+    out = {"n_workers": wl.n_workers, "n_edges": wl.n_edges, "layers": len(wl.shapes),
+           "params_per_worker": wl.params_per_worker, "rank": wl.rank, "power_steps": wl.power_steps,
+           "pg_run": {"ms_per_round": t_run, "rounds_per_s": 1e3 / t_run["median"],
+                      "bytes_per_param_per_round": bf / nparam,
+                      "GBps": bf / (t_run["median"] * 1e-3) / 1e9,
+                      "frac_of_peak": bf / (t_run["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "kernels": slim(k_fused)},
+           "pg_round": {"ms_per_round": t_round, "rounds_per_s": 1e3 / t_round["median"],
+                        "bytes_per_param_per_round": bu / nparam,
+                        "GBps": bu / (t_round["median"] * 1e-3) / 1e9,
+                        "frac_of_peak": bu / (t_round["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "kernels": slim(k_unfused)}}
+    if src:
+        out["traffic_bytes_per_launch"] = traffic
+        out["traffic_source"] = src
+    gb.close()
+    del gb
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="vgg16_r1",
-                    help="tiny | resnet20 | vgg16_r1 | vgg16_r2 | lstm | resnet50")
+                    help="headline workload: tiny | resnet20 | vgg16_r1 | vgg16_r2 | lstm | resnet50")
+    ap.add_argument("--others", default="all",
+                    help="'all', 'none' or a comma list: configurations measured beside the headline")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
-    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
-                    help="also run a plain device copy of this many MiB (known traffic, for scaling "
-                         "hardware byte counters in a rocprofv3 --pmc run)")
+    ap.add_argument("--counters", type=int, default=0, metavar="MiB",
+                    help="hardware-counter run (under rocprofv3 --pmc): only pg_run and pg_round of the "
+                         "headline workload, then 5 plain device copies of this many MiB (known traffic "
+                         "that scales the byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all simulated workers share its HBM); "
@@ -79,7 +168,6 @@ def main():
     wl = W.get(args.workload)
     gb = GossipBuffers.from_workload(wl)
     K, Wm = args.steps, args.warmup
-    stream = torch.cuda.current_stream()
 
     # ---- timed region: K consecutive rounds, fused pipeline -------------------------------
     if Wm > 0:
@@ -91,65 +179,77 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / K
 
-    # ---- the same K rounds as isolated pg_round calls (no cross-round fusion) -------------
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(K):
-        gb.round()
-    torch.cuda.synchronize()
-    dt_unfused = time.perf_counter() - t0
+    if args.counters > 0:
+        for _ in range(K):
+            gb.round()
+        torch.cuda.synchronize()
+        n = args.counters * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"counters_run": True, "workload": wl.name, "steps": K, "warmup": Wm,
+                          "copy_calibration": {"MiB": args.counters, "dispatches": 5,
+                                               "bytes_read": 4 * n, "bytes_written": 4 * n}}))
+        gb.close()
+        return
+
+    # the same pipeline again as 5 event-timed calls (spread of the per-round time)
+    stats_fused = event_times(lambda: gb.run(K), 5, K)
+    # ---- the same rounds as isolated pg_round calls (no cross-round fusion) ---------------
+    gb.round()
+    stats_unfused = event_times(lambda: gb.round(), K, 1)
 
     # ---- per-kernel durations: HIP events on the launch stream, both pipelines ------------
-    def profile(fn):
-        B.pg_profile_enable(gb.ctx, True)
-        fn()
-        torch.cuda.synchronize()
-        rows = B.pg_profile_collect(gb.ctx)
-        B.pg_profile_enable(gb.ctx, False)
-        out = {}
-        for r in rows:
-            gbs = r["bytes"] / (r["ms"] * 1e-3) / 1e9 if r["ms"] > 0 else 0.0
-            out[r["name"]] = {"launches": r["launches"], "avg_ms": r["ms"] / max(1, r["launches"]),
-                              "total_ms": r["ms"], "algorithmic_bytes_per_launch": r["bytes"] / max(1, r["launches"]),
-                              "GBps": gbs, "frac_of_peak": gbs / HBM_PEAK_GBS}
-        return out
-
     Kp = min(K, 50)
-    k_fused = profile(lambda: gb.run(Kp))
-    k_unfused = profile(lambda: [gb.round() for _ in range(Kp)])
+    k_fused = kernel_table(B, gb, lambda: gb.run(Kp))
+    k_unfused = kernel_table(B, gb, lambda: [gb.round() for _ in range(Kp)])
 
     # ---- Algorithm 1's step: the same round with the gradient term fused into the update ----
     gb.alloc_grads()
     for g in gb.g:
         g.normal_(0.0, 1e-3)
     gb.round_sgd(0.1)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(Kp):
-        gb.round_sgd(0.1)
-    torch.cuda.synchronize()
-    dt_sgd = time.perf_counter() - t0
-    k_sgd = profile(lambda: [gb.round_sgd(0.1) for _ in range(Kp)])
+    stats_sgd = event_times(lambda: gb.round_sgd(0.1), Kp, 1)
+    k_sgd = kernel_table(B, gb, lambda: [gb.round_sgd(0.1) for _ in range(min(Kp, 10))])
 
     # ---- Algorithm 2 one iteration per call (the paper's "1 iteration" setting), with gradient
     gb.alloc_pstate()
     gb.iterate(0, 1, 0.1)
     gb.iterate(1, 1, 0.1)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(2, 2 + 2 * Kp):
-        gb.iterate(k, 1, 0.1)
-    torch.cuda.synchronize()
-    dt_it = time.perf_counter() - t0
+    it = [2]
 
+    def one_iteration():
+        gb.iterate(it[0], 1, 0.1)
+        it[0] += 1
+    stats_it = event_times(one_iteration, 2 * Kp, 1)
+
+    traffic, traffic_src = traffic_from_profiles(wl.name)
     # the dominant kernel of the timed (fused) pipeline
     dom = max(k_fused.items(), key=lambda kv: kv[1]["total_ms"])
     roofline = {"bound": "hbm", "kernel": dom[0], "achieved": dom[1]["GBps"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": dom[1]["GBps"] / HBM_PEAK_GBS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom[0])),
+                "traffic": traffic.get(dom[0]), "traffic_source": traffic_src,
                 "algorithmic_bytes_per_launch": dom[1]["algorithmic_bytes_per_launch"],
                 "avg_launch_ms": dom[1]["avg_ms"]}
+    # the two sweeps the 70 % target is stated for, where each runs in its pipeline
+    sp, sq_u = k_unfused.get("sweep_p"), k_unfused.get("sweep_q")
+    sq_f = k_fused.get("sweep_q")
+    sweeps = {
+        "sweep_p_in_pg_round": sp and {"GBps": sp["GBps"], "frac": sp["frac_of_peak"], "avg_ms": sp["avg_ms"],
+                                       "runs_after": "the previous round's update (a pass that wrote every parameter)"},
+        "sweep_q_in_pg_round": sq_u and {"GBps": sq_u["GBps"], "frac": sq_u["frac_of_peak"], "avg_ms": sq_u["avg_ms"],
+                                         "runs_after": "the P-sweep (a read-only pass)"},
+        "sweep_q_in_pg_run": sq_f and {"GBps": sq_f["GBps"], "frac": sq_f["frac_of_peak"], "avg_ms": sq_f["avg_ms"],
+                                       "runs_after": "the fused update + P-sweep (a pass that wrote every parameter)"},
+        "target_frac": TARGET_FRAC,
+    }
+    fr = [v["frac"] for k, v in sweeps.items() if isinstance(v, dict)]
+    sweeps["target_met"] = bool(fr) and min(fr) >= TARGET_FRAC
+    sweeps["target_met_where"] = {k: v["frac"] >= TARGET_FRAC for k, v in sweeps.items() if isinstance(v, dict)}
 
+    nparam = wl.n_workers * wl.params_per_worker
     bytes_fused = B.pg_round_bytes(gb.ctx, True)
     bytes_unfused = B.pg_round_bytes(gb.ctx, False)
     result = {
@@ -169,19 +269,22 @@ def main():
                    "layers": len(wl.shapes), "params_per_worker": wl.params_per_worker,
                    "rank": wl.rank, "power_steps": wl.power_steps,
                    "storage": "f32", "accumulate": "f64", "pipeline": "pg_run (fused update + next sweep)"},
+        "ms_per_step_events": stats_fused,
         "round_GBps": bytes_fused / (ms_per_step * 1e-3) / 1e9,
         "round_frac_of_peak": bytes_fused / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "bytes_per_param_per_round": bytes_fused / (wl.n_workers * wl.params_per_worker),
-        "pg_round_unfused": {"rounds_per_s": K / dt_unfused, "ms_per_step": dt_unfused * 1e3 / K,
-                             "GBps": bytes_unfused / (dt_unfused / K) / 1e9,
-                             "bytes_per_param_per_round": bytes_unfused / (wl.n_workers * wl.params_per_worker)},
-        "pg_round_sgd": {"rounds_per_s": Kp / dt_sgd, "ms_per_step": dt_sgd * 1e3 / Kp,
-                         "bytes_per_param_per_round": (bytes_unfused / (wl.n_workers * wl.params_per_worker)) + 4,
+        "bytes_per_param_per_round": bytes_fused / nparam,
+        "sweeps": sweeps,
+        "pg_round_unfused": {"ms_per_step": stats_unfused, "rounds_per_s": 1e3 / stats_unfused["median"],
+                             "GBps": bytes_unfused / (stats_unfused["median"] * 1e-3) / 1e9,
+                             "bytes_per_param_per_round": bytes_unfused / nparam},
+        "pg_round_sgd": {"ms_per_step": stats_sgd, "rounds_per_s": 1e3 / stats_sgd["median"],
+                         "bytes_per_param_per_round": bytes_unfused / nparam + 4,
                          "update_sgd_kernel": k_sgd.get("update_sgd")},
-        "pg_iterate_1_sgd": {"iterations_per_s": 2 * Kp / dt_it, "ms_per_iteration": dt_it * 1e3 / (2 * Kp),
+        "pg_iterate_1_sgd": {"ms_per_iteration": stats_it, "iterations_per_s": 1e3 / stats_it["median"],
                              "bytes_per_param_per_iteration": 16.0,
-                             "GBps": 16.0 * wl.n_workers * wl.params_per_worker / (dt_it / (2 * Kp)) / 1e9},
+                             "GBps": 16.0 * nparam / (stats_it["median"] * 1e-3) / 1e9},
         "roofline": roofline,
+        "traffic_bytes_per_launch": traffic or None,
         "kernels_fused": k_fused,
         "kernels_unfused": k_unfused,
     }
@@ -204,15 +307,13 @@ def main():
                               "what": "torch device-to-device copy of 1 GiB, bytes read + bytes written per second"}
     del src, dst
     torch.cuda.empty_cache()
-    if args.copy_calibration > 0:
-        n = args.copy_calibration * (1 << 20) // 4
-        src = torch.ones(n, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        result["copy_calibration"] = {"MiB": args.copy_calibration, "bytes_read": 4 * n, "bytes_written": 4 * n}
-        del src, dst
+
+    # ---- the other named configurations ---------------------------------------------------
+    names = [n for n in W.NAMES if n != wl.name] if args.others == "all" else \
+        ([] if args.others in ("none", "") else [n.strip() for n in args.others.split(",")])
+    rounds_for = {"tiny": 200, "resnet20": 200, "vgg16_r1": 50, "vgg16_r2": 50, "lstm": 20, "resnet50": 10}
+    result["other_workloads"] = {n: measure_other(n, rounds_for.get(n, 20)) for n in names}
+
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
     else:

@@ -93,9 +93,13 @@ int pg_destroy(pg_ctx *ctx);
 /*
  * Layout queries (host, no HIP call).
  *
- * A worker's parameter buffer is `pg_param_floats` floats; layer l is the row-major
- * p_l x q_l block starting at float `pg_layer_offset(l)`.  Offsets are multiples of 4 floats;
- * the padding between layers is never read or written.
+ * A worker's parameter buffer is `pg_param_floats` floats; layer l is a row-major p_l x q_l
+ * matrix starting at float `pg_layer_offset(l)` whose rows are `pg_layer_stride(l)` >= q_l floats
+ * apart: element (row, c) is float offset + row * stride + c.  The stride is q_l, except for
+ * layers that run with 8 or more stacked columns (deg(i) * r_l), whose rows are padded to whole
+ * 128-byte lines (stride = q_l rounded up to a multiple of 32).  Offsets are multiples of 32
+ * floats; padding, between rows or between layers, is never read or written.  Gradient buffers
+ * (pg_round_sgd, pg_iterate) use the same layout.
  *
  * The state buffer is `pg_qstate_floats` floats; the block of edge e, layer l starts at float
  * `pg_q_offset(e, l)` (a multiple of 4) and holds r_l columns of q_l floats each, column k at
@@ -105,6 +109,7 @@ int pg_destroy(pg_ctx *ctx);
  */
 size_t pg_param_floats(const pg_ctx *ctx);
 size_t pg_layer_offset(const pg_ctx *ctx, int layer);
+size_t pg_layer_stride(const pg_ctx *ctx, int layer);
 int pg_layer_rank(const pg_ctx *ctx, int layer);
 size_t pg_qstate_floats(const pg_ctx *ctx);
 size_t pg_q_offset(const pg_ctx *ctx, int edge, int layer);
@@ -143,7 +148,8 @@ int pg_upload(pg_ctx *ctx);
 /*
  * One gossip round.
  *   worker_params  host array of n_workers DEVICE pointers, each to pg_param_floats floats,
- *                  16-byte aligned; updated in place.  The pointer values are cached; a call
+ *                  16-byte aligned (128-byte alignment lets padded rows start on cache lines);
+ *                  updated in place.  The pointer values are cached; a call
  *                  with different values re-uploads the table (a synchronous copy).
  *   q_state        device, pg_qstate_floats floats, 16-byte aligned; in: Q, out: Q'
  *   workspace      device, pg_workspace_bytes bytes, 256-byte aligned; contents need not persist

@@ -16,7 +16,7 @@ PG_OK, PG_ERR_ARG, PG_ERR_TOPOLOGY, PG_ERR_SHAPE, PG_ERR_NOMEM, PG_ERR_DEVICE, P
 PG_STATIC_WORKSPACE_BYTES = 32 << 20
 
 EXPORTS = [
-    "pg_strerror", "pg_init", "pg_destroy", "pg_param_floats", "pg_layer_offset", "pg_layer_rank",
+    "pg_strerror", "pg_init", "pg_destroy", "pg_param_floats", "pg_layer_offset", "pg_layer_stride", "pg_layer_rank",
     "pg_qstate_floats", "pg_q_offset", "pg_workspace_bytes", "pg_ws_phat_offset",
     "pg_ws_flag_offset", "pg_message_floats", "pg_round_bytes", "pg_upload", "pg_round", "pg_round_static", "pg_round_sgd",
     "pg_run", "pg_iterate", "pg_pstate_floats", "pg_p_offset",
@@ -60,7 +60,7 @@ def _load():
     lib.pg_init.argtypes = [ctypes.POINTER(vp), ci, ci, vp, vp, ci, vp, vp, ci, ci]
     lib.pg_destroy.restype = ci
     lib.pg_destroy.argtypes = [vp]
-    for name, args in [("pg_param_floats", [vp]), ("pg_layer_offset", [vp, ci]),
+    for name, args in [("pg_param_floats", [vp]), ("pg_layer_offset", [vp, ci]), ("pg_layer_stride", [vp, ci]),
                        ("pg_qstate_floats", [vp]), ("pg_q_offset", [vp, ci, ci]),
                        ("pg_workspace_bytes", [vp]), ("pg_ws_phat_offset", [vp, ci, ci]),
                        ("pg_ws_flag_offset", [vp, ci, ci]), ("pg_message_floats", [vp])]:
@@ -133,6 +133,7 @@ def pg_destroy(ctx: int) -> None:
 
 def pg_param_floats(ctx): return lib.pg_param_floats(ctx)
 def pg_layer_offset(ctx, layer): return lib.pg_layer_offset(ctx, layer)
+def pg_layer_stride(ctx, layer): return lib.pg_layer_stride(ctx, layer)
 def pg_layer_rank(ctx, layer): return lib.pg_layer_rank(ctx, layer)
 def pg_qstate_floats(ctx): return lib.pg_qstate_floats(ctx)
 def pg_q_offset(ctx, edge, layer): return lib.pg_q_offset(ctx, edge, layer)

@@ -338,7 +338,8 @@ struct Launcher {
         begin(K_ORTH_P, 0.0);
         const int rmax = c->plan.max_layer_rank;
         // short layers: small work-groups, so that many (edge, layer) pairs share a CU
-        const bool small = c->plan.max_rows <= 2048;
+        // (row chunks of tall layers are sized for 256 threads as well)
+        const bool small = c->plan.max_rows <= 2048 || !c->plan.orth_tiles.empty();
         if (rmax <= 1) small ? orth_launch<256, 1>() : orth_launch<kOrthThreads, 1>();
         else if (rmax <= 2) small ? orth_launch<256, 2>() : orth_launch<kOrthThreads, 2>();
         else if (rmax <= 4) small ? orth_launch<256, 4>() : orth_launch<kOrthThreads, 4>();
@@ -518,6 +519,10 @@ size_t pg_param_floats(const pg_ctx *c) { return c ? c->plan.param_floats : (siz
 size_t pg_layer_offset(const pg_ctx *c, int l) {
     if (!c || l < 0 || l >= c->plan.n_layers) return (size_t)-1;
     return (size_t)c->plan.layers[l].x_off;
+}
+size_t pg_layer_stride(const pg_ctx *c, int l) {
+    if (!c || l < 0 || l >= c->plan.n_layers) return (size_t)-1;
+    return (size_t)c->plan.layers[l].ld;
 }
 int pg_layer_rank(const pg_ctx *c, int l) {
     if (!c || l < 0 || l >= c->plan.n_layers) return -1;

@@ -31,7 +31,7 @@ struct ColDesc {
 // One (worker, layer) pair.
 struct PairDesc {
     int32_t worker, p, q, R;
-    int64_t x_off;     // float offset of the layer inside a worker buffer
+    int64_t x_off;     // float offset of the layer inside a worker buffer (rows are ld floats apart)
     int64_t pw_off;    // double offset of this pair's partial products X_i S: [seg][j][row]
     int64_t qw_off;    // double offset of this pair's partial products X_i^T T: [blk][j][c]
     int32_t col0;      // first ColDesc of the pair (R consecutive entries)
@@ -43,7 +43,7 @@ struct PairDesc {
     int32_t blk_rows;  // rows per block
     int32_t V;         // floats per vector load on this layer: 4, 2 or 1 (largest that divides q)
     int32_t wc;        // matrix-core row tiles: wavefronts side by side over the column steps (1, 2 or 4)
-    int32_t pad;
+    int32_t ld;        // floats from one row of the layer to the next in a worker buffer (>= q)
 };
 
 // Row-owner tile: rows [row0, row0 + nrows) x column segment seg of one pair.
@@ -75,7 +75,8 @@ struct EdgeLayerDesc {
 struct OrthTile {
     int32_t el, row0, nrows, chunk, nchunks, pad;
 };
-constexpr int kOrthChunkRows = 4096;
+constexpr int kOrthTallRows = 4096;   // layers taller than this are orthonormalised chunk by chunk
+constexpr int kOrthChunkRows = 1024;  // rows per chunk (one work-group of 256 threads)
 
 // combine_q tile: 256 consecutive elements of the r*q block of one (edge, layer).
 struct CombTile {

@@ -40,6 +40,12 @@ __device__ __forceinline__ void stg(float *p, typename VecT<V>::T v) {
 }
 __device__ __forceinline__ float ldg1(const float *p) { return *(const PG_GLOBAL float *)p; }
 
+// Which tile this work-group takes: the tile list in order, or backwards, so that a pass can start
+// on the data the previous pass touched last (still resident in the memory-side cache).
+__device__ __forceinline__ int tile_index(int ntiles, int reverse) {
+    return reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x;
+}
+
 // ---- wavefront reductions on the DPP / swizzle network --------------------------------
 template <int CTRL>
 __device__ __forceinline__ double dpp_mov(double v) {
@@ -148,8 +154,8 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
         for (int m = 0; m < M; ++m) {
             ok[m] = rbase + m < row_end;
             rowi[m] = ok[m] ? rbase + m : row_end - 1;
-            xrow[m] = X + (int64_t)rowi[m] * q;
-            grow[m] = GRAD ? Gp + (int64_t)rowi[m] * q : nullptr;
+            xrow[m] = X + (int64_t)rowi[m] * pd.ld;
+            grow[m] = GRAD ? Gp + (int64_t)rowi[m] * pd.ld : nullptr;
         }
         double cp[M][RC];
         if (UPDATE) {
@@ -264,7 +270,7 @@ row_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
            float *const *__restrict__ xs, const float *__restrict__ qstate,
            const float *__restrict__ phat, double *__restrict__ pw,
            const float *const *__restrict__ gs, double eta) {
-    const RowTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
+    const RowTile t = tiles[tile_index(ntiles, reverse)];
     const PairDesc pd = pairs[t.pair];
     float *X = xs[pd.worker] + pd.x_off;
     const float *Gp = GRAD ? gs[pd.worker] + pd.x_off : nullptr;
@@ -337,8 +343,8 @@ __device__ __forceinline__ void row_wide_body(const RowTile &t, const PairDesc &
         for (int m = 0; m < M; ++m) {
             ok[m] = rbase + m < row_end;
             rowi[m] = ok[m] ? rbase + m : row_end - 1;
-            xrow[m] = X + (int64_t)rowi[m] * q;
-            grow[m] = GRAD ? Gp + (int64_t)rowi[m] * q : nullptr;
+            xrow[m] = X + (int64_t)rowi[m] * pd.ld;
+            grow[m] = GRAD ? Gp + (int64_t)rowi[m] * pd.ld : nullptr;
         }
         double cp[M][RC];
         if (UPDATE) {
@@ -455,7 +461,7 @@ row_wide_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
                 const float *const *__restrict__ gs, double eta) {
     extern __shared__ double smem[];
     float *sQ = reinterpret_cast<float *>(smem);
-    const RowTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
+    const RowTile t = tiles[tile_index(ntiles, reverse)];
     const PairDesc pd = pairs[t.pair];
     float *X = xs[pd.worker] + pd.x_off;
     const float *Gp = GRAD ? gs[pd.worker] + pd.x_off : nullptr;
@@ -568,14 +574,15 @@ struct BoolTag {
     static constexpr bool value = B;
 };
 // Two work-groups per CU: left alone the compiler takes every register it can (one work-group).
+// (measured: the sweep alone is 11 % faster at three wavefronts per SIMD, one register spilled).
 template <int V, int RCM, int MB, int D, bool UPDATE, bool SWEEP, bool GRAD>
-__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((UPDATE || GRAD) ? 2 : 3)))
 mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse, const PairDesc *__restrict__ pairs,
             const ColDesc *__restrict__ cols, float *const *__restrict__ xs,
             const float *__restrict__ qstate, const float *__restrict__ phat,
             double *__restrict__ pw, const float *const *__restrict__ gs, double eta) {
     extern __shared__ double smem[];
-    const RowTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
+    const RowTile t = tiles[tile_index(ntiles, reverse)];
     const PairDesc pd = pairs[t.pair];
     float *X = xs[pd.worker] + pd.x_off;
     const float *Gp = GRAD ? gs[pd.worker] + pd.x_off : nullptr;
@@ -600,7 +607,7 @@ mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse, const Pa
     for (int b = 0; b < MB; ++b)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-            roff[b][v] = 4u * (uint32_t)min(row0w + 16 * b + 4 * v + hi, row_end - 1) * (uint32_t)q;
+            roff[b][v] = 4u * (uint32_t)min(row0w + 16 * b + 4 * v + hi, row_end - 1) * (uint32_t)pd.ld;
 
     // update operand A: coef_j * Phat_j[row lo of the block], j = 4 m + hi
     const float *qup[UPDATE ? RCM : 1];
@@ -661,7 +668,6 @@ mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse, const Pa
         const int cs = c_begin + 64 * (wcol + WC * s);
         const int nvalid = c_end - cs;
         const uint32_t cso = 4u * (uint32_t)cs;
-        float bq[4][4];
         if (SWEEP) {
             // B[k][j]: layout [column / 4][j][4]; a unit of V floats stays inside one group of 4
 #pragma unroll
@@ -678,12 +684,6 @@ mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse, const Pa
                 }
             }
             wave_lds_sync();
-#pragma unroll
-            for (int s2 = 0; s2 < 4; ++s2) {
-                const VecT<4>::T tv = *reinterpret_cast<const VecT<4>::T *>(qbuf + ((4 * s2 + hi) * 16 + lo) * 4);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) bq[s2][e] = tv[e];
-            }
         }
         // columns past the row's end: the sweep must see zeros there
         bool cok[4];
@@ -723,12 +723,15 @@ mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse, const Pa
 #pragma unroll
                 for (int v = 0; v < 4; ++v) lds_put_row<V>(xb + (4 * v + hi) * kMrowXStride, lo, f.x[b][v]);
                 wave_lds_sync();
+                // the B operand is read back per block rather than kept across the blocks of a step:
+                // 16 registers less, which the fused pass would otherwise spill
 #pragma unroll
                 for (int s2 = 0; s2 < 4; ++s2) {
                     const VecT<4>::T av =
                         *reinterpret_cast<const VecT<4>::T *>(xb + lo * kMrowXStride + 16 * s2 + 4 * hi);
+                    const VecT<4>::T bv = *reinterpret_cast<const VecT<4>::T *>(qbuf + ((4 * s2 + hi) * 16 + lo) * 4);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[b] = mfma16((double)av[e], (double)bq[s2][e], acc[b]);
+                    for (int e = 0; e < 4; ++e) acc[b] = mfma16((double)av[e], (double)bv[e], acc[b]);
                     PG_FENCE();
                 }
             }
@@ -825,12 +828,12 @@ mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse, const Pa
 // D_v[col][j] += X[row][col] * Phat_j[row] (A = X^T, B = the stacked Phat columns, j = lo); a
 // lane's four Phat values of a step are consecutive in memory and come in one load.
 template <int V, int D>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
 mcol_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
             const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
             float *const *__restrict__ xs, const float *__restrict__ phat,
             double *__restrict__ qw) {
-    const ColTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
+    const ColTile t = tiles[tile_index(ntiles, reverse)];
     const PairDesc pd = pairs[t.pair];
     const float *X = xs[pd.worker] + pd.x_off;
     const int lane = threadIdx.x & 63, lo = lane & 15, hi = lane >> 4;
@@ -862,12 +865,13 @@ mcol_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
         for (int u = 0; u < 4; ++u) {
             const int r = last ? min(r0 + u, re - 1) : r0 + u;
             if (last) f.t[u] = ldg1(ph + r);
-            const float *xr = xt + (int64_t)r * q;
+            const float *xr = xt + (int64_t)r * pd.ld;
 #pragma unroll
             for (int w = 0; w < 4 / V; ++w) {
                 const int cw = 16 * V * w + V * lo;
-                // a lane past the row's end reads the row's start: that sum is not stored
-                const typename VecT<V>::T xv = ldg<V>(xr + (cw < ncols ? cw : -c0));
+                // a lane past the row's end re-reads the row's last unit (a line the valid lanes
+                // fetch anyway): that sum is not stored
+                const typename VecT<V>::T xv = ldg<V>(xr + (cw < ncols ? cw : ncols - V));
 #pragma unroll
                 for (int e = 0; e < V; ++e) f.x[u][V * w + e] = xv[e];
             }
@@ -932,8 +936,10 @@ sgd_only_kernel(const int32_t *__restrict__ pair_ids, const PairDesc *__restrict
     const float *G = gs[pd.worker] + pd.x_off;
     const int64_t total = (int64_t)pd.p * pd.q;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total;
-         i += (int64_t)gridDim.x * kThreads)
-        X[i] = (float)fma(-eta, (double)G[i], (double)X[i]);
+         i += (int64_t)gridDim.x * kThreads) {
+        const int64_t at = (i / pd.q) * pd.ld + i % pd.q;
+        X[at] = (float)fma(-eta, (double)G[at], (double)X[at]);
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -985,7 +991,7 @@ __device__ __forceinline__ void col_body(const ColTile &t, const PairDesc &pd,
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int rr = min(row + u * RG, re - 1);
-            xv[u] = ldg<V>(xcol + (int64_t)rr * q);
+            xv[u] = ldg<V>(xcol + (int64_t)rr * pd.ld);
         }
     };
     auto process = [&](int row, vec(&xv)[U]) {
@@ -1064,7 +1070,7 @@ col_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
            double *__restrict__ qw) {
     extern __shared__ double smem[];  // [blk_rows][RC] Phat floats, then reused for the reduction
     float *sT = reinterpret_cast<float *>(smem);
-    const ColTile t = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];
+    const ColTile t = tiles[tile_index(ntiles, reverse)];
     const PairDesc pd = pairs[t.pair];
     const float *X = xs[pd.worker] + pd.x_off;
     if constexpr (V != 0) {

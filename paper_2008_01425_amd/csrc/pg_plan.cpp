@@ -60,6 +60,9 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     for (int i = 0; i < n_workers; ++i)
         if (wsum[i] > 1.0 + 1e-6) return PG_ERR_ARG;  // the self-weight W_ii would be negative
 
+    size_t max_deg = 0;
+    for (int i = 0; i < n_workers; ++i) max_deg = std::max(max_deg, P.incident[i].size());
+
     // ---- layers: every weight and bias is its own matrix (Section 2) ----
     P.layers.resize(n_layers);
     int64_t off = 0;
@@ -75,8 +78,15 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         P.max_layer_rank = std::max(P.max_layer_rank, L.r);
         P.max_rows = std::max(P.max_rows, p);
         L.V = (q % 4 == 0) ? 4 : (q % 2 == 0 ? 2 : 1);
+        // Row stride.  With 8 or more stacked columns a tile's wavefronts work side by side on
+        // 64-column (256-byte) pieces of the same rows; when rows start at arbitrary addresses every
+        // piece ends inside a 128-byte line that the neighbouring wavefront touches at another time,
+        // and the line crosses the memory interface twice (measured on 650-float rows: a third more
+        // bytes read, a quarter more written).  Rows of such layers start on line boundaries.
+        const bool shared_rows = compiled_cols(std::max<int>(1, (int)max_deg * L.r)) >= kWideCols;
+        L.ld = (shared_rows && q >= 64) ? (int)round_up(q, 32) : q;
         L.x_off = off;
-        off = round_up(off + (int64_t)p * q, 4);
+        off = round_up(off + (int64_t)p * L.ld, 32);
         P.elems_per_worker += (double)p * q;
         P.message_floats += (size_t)L.r * ((size_t)p + q);
     }
@@ -133,13 +143,11 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         Geo &g = geo[l];
         int nv = L.q / L.V;  // vector loads per row
         // The row blocking depends on the stacked column count; size for the best-connected worker.
-        size_t max_deg = 0;
-        for (int i = 0; i < n_workers; ++i) max_deg = std::max(max_deg, P.incident[i].size());
         int rc_max = compiled_cols(std::max<int>(1, (int)max_deg * L.r));
         g.wide = rc_max >= kWideCols;
         // Row passes on the matrix cores pay from 16 stacked columns on (measured: at 8 the vector
         // kernels' P-sweep is the faster one) and address a layer with 32-bit byte offsets.
-        g.mrow = tune.mfma_rows && rc_max >= kMfmaRowCols && (int64_t)L.p * L.q < ((int64_t)1 << 30);
+        g.mrow = tune.mfma_rows && rc_max >= kMfmaRowCols && (int64_t)L.p * L.ld < ((int64_t)1 << 30);
         // Lanes per row: a whole wavefront for few stacked columns; 16 for many, where the
         // per-row lane reduction (RC values per row) would otherwise rival the products.
         g.lpr = std::min((g.wide && !g.mrow) ? 16 : 64, pow2_ceil(nv));
@@ -229,7 +237,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             pd.blk_rows = g.blk_rows;
             pd.V = L.V;
             pd.wc = g.wc;
-            pd.pad = 0;
+            pd.ld = L.ld;
             pwo += (int64_t)g.nseg * pd.R * L.p;
             qwo += (int64_t)g.nblk * pd.R * L.q;
             for (int e : P.incident[i])
@@ -301,7 +309,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     // tall layers: row chunks for the two-kernel orthonormalisation (36 Gram sums per chunk)
     P.orth_tiles.clear();
     bool tall = false;
-    for (int l = 0; l < n_layers; ++l) tall = tall || P.layers[l].p > kOrthChunkRows;
+    for (int l = 0; l < n_layers; ++l) tall = tall || P.layers[l].p > kOrthTallRows;
     if (tall) {
         for (size_t el = 0; el < P.els.size(); ++el) {
             const int p = P.els[el].p;

@@ -12,6 +12,8 @@ namespace pg {
 struct LayerInfo {
     int p, q, r;        // r = min(rank, p, q)
     int V;              // floats per vector load: 4, 2 or 1 (largest that divides q)
+    int ld;             // row stride in a worker buffer, floats: q, or q rounded up to a whole number of
+                        // 128-byte lines where several wavefronts share the rows of a tile
     int64_t x_off;      // float offset inside a worker buffer
 };
 

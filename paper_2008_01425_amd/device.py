@@ -45,15 +45,18 @@ class GossipBuffers:
             self.ctx = None
 
     # ---- host <-> device, layer by layer --------------------------------
+    def _layer_view(self, buf: torch.Tensor, l: int) -> torch.Tensor:
+        """The p x q matrix of layer l inside a worker buffer (rows pg_layer_stride floats apart)."""
+        p, q = self.shapes[l]
+        off, ld = B.pg_layer_offset(self.ctx, l), B.pg_layer_stride(self.ctx, l)
+        return buf[off:off + p * ld].view(p, ld)[:, :q]
+
     def set_layer(self, i: int, l: int, a: np.ndarray):
         p, q = self.shapes[l]
-        off = B.pg_layer_offset(self.ctx, l)
-        self.x[i][off:off + p * q].copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32).reshape(-1)))
+        self._layer_view(self.x[i], l).copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32).reshape(p, q)))
 
     def get_layer(self, i: int, l: int) -> np.ndarray:
-        p, q = self.shapes[l]
-        off = B.pg_layer_offset(self.ctx, l)
-        return self.x[i][off:off + p * q].cpu().numpy().reshape(p, q)
+        return self._layer_view(self.x[i], l).cpu().numpy()
 
     def set_q(self, e: int, l: int, a: np.ndarray):
         r, q = self.ranks[l], self.shapes[l][1]
@@ -111,8 +114,7 @@ class GossipBuffers:
 
     def set_grad_layer(self, i: int, l: int, a: np.ndarray):
         p, q = self.shapes[l]
-        off = B.pg_layer_offset(self.ctx, l)
-        self.g[i][off:off + p * q].copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32).reshape(-1)))
+        self._layer_view(self.g[i], l).copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32).reshape(p, q)))
 
     def round_sgd(self, eta: float, stream: Optional[torch.cuda.Stream] = None):
         s = torch.cuda.current_stream(self.device) if stream is None else stream

@@ -82,13 +82,13 @@ def test_layouts_are_aligned_disjoint_and_complete():
     L, E = len(wl.shapes), wl.n_edges
     spans = []
     for l, (p, q) in enumerate(wl.shapes):
-        off = B.pg_layer_offset(ctx, l)
-        assert off % 4 == 0
+        off, ld = B.pg_layer_offset(ctx, l), B.pg_layer_stride(ctx, l)
+        assert off % 32 == 0 and ld == q          # a ring at rank 2: 4 stacked columns, no row padding
         assert B.pg_layer_rank(ctx, l) == min(2, p, q)
-        spans.append((off, off + p * q))
+        spans.append((off, off + p * ld))
     spans.sort()
     assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
-    assert spans[-1][1] <= B.pg_param_floats(ctx) < spans[-1][1] + 4
+    assert spans[-1][1] <= B.pg_param_floats(ctx) < spans[-1][1] + 32
     qsp = []
     for e in range(E):
         for l, (p, q) in enumerate(wl.shapes):
@@ -129,6 +129,28 @@ def test_workload_shapes_and_byte_accounting(name, N, mats):
     assert B.pg_round_bytes(ctx, False) == 4.0 * wl.n_workers * N * (2 * s + 2)
     assert B.pg_round_bytes(ctx, True) == 4.0 * wl.n_workers * N * (2 * s + 1)
     assert B.pg_message_floats(ctx) == sum(min(wl.rank, p, q) * (p + q) for p, q in wl.shapes)
+    B.pg_destroy(ctx)
+
+
+def test_rows_are_padded_to_whole_lines_only_where_wavefronts_share_rows():
+    """8 or more stacked columns (here: 4 x 4 torus at rank 4, and at rank 2): rows of layers with
+    at least 64 columns start on 128-byte boundaries; elsewhere the stride is the row length."""
+    wl = W.get("lstm")
+    ctx = _init(wl.n_workers, wl.edges, wl.edge_w, [(33278, 650), (2600, 650), (40, 63), (100, 64), (7, 1)], 4, 2)
+    assert [B.pg_layer_stride(ctx, l) for l in range(5)] == [672, 672, 63, 64, 1]
+    end = 0
+    for l, (p, q) in enumerate([(33278, 650), (2600, 650), (40, 63), (100, 64), (7, 1)]):
+        off = B.pg_layer_offset(ctx, l)
+        assert off % 32 == 0 and off >= end
+        end = off + p * B.pg_layer_stride(ctx, l)
+    assert end <= B.pg_param_floats(ctx)
+    assert B.pg_layer_stride(ctx, 5) == ctypes.c_size_t(-1).value
+    B.pg_destroy(ctx)
+    ctx = _init(5, W.ring_edges(5), 1 / 3, [(2600, 650)], 4, 1)     # 8 stacked columns
+    assert B.pg_layer_stride(ctx, 0) == 672
+    B.pg_destroy(ctx)
+    ctx = _init(5, W.ring_edges(5), 1 / 3, [(2600, 650)], 2, 1)     # 4 stacked columns: one wavefront per row group
+    assert B.pg_layer_stride(ctx, 0) == 650
     B.pg_destroy(ctx)
 
 

@@ -80,7 +80,10 @@ const char *pg_strerror(int status);
  *                sum over its edges must be <= 1 + 1e-6 (its self-weight W_ii stays >= 0, A4)
  *   n_layers     L >= 1
  *   rows, cols   host, [n_layers] int32: p_l, q_l (q_l = 1 for vectors)
- *   rank         r >= 1 (r_l = min(r, p_l, q_l)); deg(i) * r_l must be <= 16 for every worker
+ *   rank         r >= 1 (r_l = min(r, p_l, q_l)); r_l must be <= 16.  A worker whose stacked
+ *                columns deg(i) * r_l exceed 16 is handled in groups of whole edges, one pass over
+ *                its matrix per group and product; its update is then applied group by group,
+ *                each pass rounding the parameters to float once, and pg_run does not fuse
  *   power_steps  s >= 1
  * All host arrays are copied; the caller may free them on return.
  */

@@ -8,9 +8,11 @@ each worker starts from a 100 x 100 standard-normal matrix), run on the GPU libr
 Prints the consensus error (1/n) sum_i |X_i - mean|_F^2 against bits sent per worker for
   * PowerGossip with the warm-started power iteration (pg_round, one power step = 2 iterations),
   * the same compressor with a fresh N(0,1) projection every round (random projections),
-  * the literal one-iteration-per-round schedule (pg_iterate),
-  * uncompressed gossip X <- W X (rank = min(p, q): the projector is the identity).
-The Faces half of the figure needs a dataset and is not reproduced.
+  * the literal one-iteration-per-round schedule (pg_iterate).
+Every step of every variant runs in the library's kernels; this module only draws the seeded
+inputs (`initial_matrices`, `projection_stream`) and reads the error back.  Uncompressed gossip
+(a full-rank projector, rank 100 here) is beyond the library's 16 columns per edge and is not
+part of this program; the Faces half of the figure needs a dataset and is not reproduced.
 """
 from __future__ import annotations
 
@@ -28,36 +30,39 @@ def consensus_error(gb: GossipBuffers) -> float:
     return float(((x - x.mean(0, keepdim=True)) ** 2).sum() / gb.n)
 
 
+def initial_matrices(n: int, p: int, q: int, seed: int):
+    """X_i ~ N(0, 1) entry-wise, one (p, q) float32 matrix per worker."""
+    rng = np.random.default_rng([seed, 1])
+    return [rng.standard_normal((p, q)).astype(np.float32) for _ in range(n)]
+
+
+def projection_stream(n_edges: int, rank: int, q: int, seed: int):
+    """Generator of projection states: every item is a list of n_edges (rank, q) float32 arrays,
+    entry-wise N(0, 1) (the initialisation of Algorithm 2; drawn afresh for random projections)."""
+    rng = np.random.default_rng([seed, 2])
+    while True:
+        yield [rng.standard_normal((rank, q)).astype(np.float32) for _ in range(n_edges)]
+
+
+VARIANTS = ("power_iteration", "random_projection", "one_iteration")
+
+
 def run(rounds: int = 300, rank: int = 1, n: int = 8, p: int = 100, q: int = 100, w: float = 0.436,
         seed: int = 0, every: int = 25):
+    """{variant: [(round, bits sent per worker so far, consensus error)]}."""
     edges = W.ring_edges(n)
     ew = np.full((n,), w, dtype=np.float32)
-    rng = np.random.default_rng(seed)
-    X0 = [rng.standard_normal((p, q)).astype(np.float32) for _ in range(n)]
-    gen = torch.Generator(device="cuda").manual_seed(seed)
+    X0 = initial_matrices(n, p, q, seed)
     deg = 2
     out = {}
-    for name in ("power_iteration", "random_projection", "one_iteration", "uncompressed"):
-        r = min(p, q) if name == "uncompressed" and deg * min(p, q) <= 16 else rank
-        if name == "uncompressed":
-            # the full-rank projector needs deg * min(p, q) stacked columns; past the library's 16
-            # this baseline is evaluated in closed form, X <- W X, on the host
-            Wm = np.zeros((n, n))
-            for a, b in edges:
-                Wm[a, b] = Wm[b, a] = w
-            Wm += np.diag(1 - Wm.sum(1))
-            X = np.stack(X0).astype(np.float64)
-            curve = []
-            for t in range(rounds + 1):
-                if t % every == 0:
-                    curve.append((t, t * deg * p * q * 32, float(((X - X.mean(0)) ** 2).sum() / n)))
-                X = np.einsum("ij,jpq->ipq", Wm, X)
-            out[name] = curve
-            continue
-        gb = GossipBuffers(n, edges, ew, [(p, q)], r, 1)
+    for name in VARIANTS:
+        gb = GossipBuffers(n, edges, ew, [(p, q)], rank, 1)
+        r = gb.ranks[0]
         for i in range(n):
             gb.set_layer(i, 0, X0[i])
-        gb.q.normal_(0, 1, generator=gen)
+        states = projection_stream(n, r, q, seed)
+        for e, a in enumerate(next(states)):
+            gb.set_q(e, 0, a)
         if name == "one_iteration":
             gb.alloc_pstate()
         curve = []
@@ -69,7 +74,8 @@ def run(rounds: int = 300, rank: int = 1, n: int = 8, p: int = 100, q: int = 100
                 gb.round()
                 bits += deg * r * (p + q) * 32
             elif name == "random_projection":
-                gb.q.normal_(0, 1, generator=gen)
+                for e, a in enumerate(next(states)):
+                    gb.set_q(e, 0, a)
                 gb.round()
                 bits += deg * r * (p + q) * 32
             else:

@@ -246,13 +246,15 @@ struct Launcher {
         for (size_t k = 0; k < classes.size(); ++k) {
             const RowClass &rc = classes[c->reverse ? classes.size() - 1 - k : k];
             if (rc.tiles.empty()) continue;
-            begin(kind, rc.elems * 4.0 * (grad ? 3.0 : (upd ? 2.0 : 1.0)));
+            // a worker with several column groups: the gradient enters with the first group only
+            const bool g = grad && rc.group == 0;
+            begin(kind, rc.elems * 4.0 * (g ? 3.0 : (upd ? 2.0 : 1.0)));
             switch (rc.RC) {
-                case 1: row_mode<1>(rc, upd, swp, grad); break;
-                case 2: row_mode<2>(rc, upd, swp, grad); break;
-                case 4: row_mode<4>(rc, upd, swp, grad); break;
-                case 8: row_mode<8>(rc, upd, swp, grad); break;
-                default: row_mode<16>(rc, upd, swp, grad); break;
+                case 1: row_mode<1>(rc, upd, swp, g); break;
+                case 2: row_mode<2>(rc, upd, swp, g); break;
+                case 4: row_mode<4>(rc, upd, swp, g); break;
+                case 8: row_mode<8>(rc, upd, swp, g); break;
+                default: row_mode<16>(rc, upd, swp, g); break;
             }
             check();
             end();
@@ -431,6 +433,9 @@ int run_rounds(pg_ctx *c, float *const *worker_params, float *q_state, void *wor
     Launcher L{c, st, q_state, (char *)workspace};
     L.quiet = !may_allocate;
     const int s = c->plan.steps;
+    // Several column groups per worker: the update takes one pass per group, so no single pass
+    // sees the finished parameters together with all of a worker's columns; rounds run unfused.
+    if (c->plan.max_groups > 1) fuse = false;
     // Measured: with the passes that write (update + sweep) walking forwards and the Q-sweeps
     // backwards a run of fused rounds is 4 % faster than its mirror image, so a run starts forwards.
     if (fuse) c->reverse = 0;
@@ -476,6 +481,7 @@ int pg_init(pg_ctx **out, int n_workers, int n_edges, const int32_t *edges, cons
     if (const char *e = getenv("PG_WIDE_TILE_BYTES")) tune.wide_tile_bytes = std::max(1024, atoi(e));
     if (const char *e = getenv("PG_MFMA_ROWS")) tune.mfma_rows = atoi(e) != 0;
     if (const char *e = getenv("PG_MFMA_COLS")) tune.mfma_cols = atoi(e) != 0;
+    if (const char *e = getenv("PG_MFMA_ROW_COLS")) tune.mfma_row_cols = atoi(e) <= 8 ? 8 : 16;
     int rc;
     try {
         rc = build_plan(c->plan, n_workers, n_edges, edges, edge_w, n_layers, rows, cols, rank,
@@ -550,6 +556,8 @@ size_t pg_ws_flag_offset(const pg_ctx *c, int e, int l) {
 size_t pg_message_floats(const pg_ctx *c) { return c ? c->plan.message_floats : (size_t)-1; }
 double pg_round_bytes(const pg_ctx *c, int fused) {
     if (!c) return -1.0;
+    if (c->plan.max_groups > 1)  // one pass per column group, never fused
+        return 4.0 * c->plan.pass_elems * (2 * c->plan.steps + 2);
     int passes = 2 * c->plan.steps + (fused ? 1 : 2);
     return 4.0 * c->plan.n * c->plan.elems_per_worker * passes;
 }

@@ -83,7 +83,8 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         // piece ends inside a 128-byte line that the neighbouring wavefront touches at another time,
         // and the line crosses the memory interface twice (measured on 650-float rows: a third more
         // bytes read, a quarter more written).  Rows of such layers start on line boundaries.
-        const bool shared_rows = compiled_cols(std::max<int>(1, (int)max_deg * L.r)) >= kWideCols;
+        const int per_pass = std::min<int>((int)max_deg, std::max(1, kMaxCols / L.r));  // edges one pass takes
+        const bool shared_rows = compiled_cols(std::max(1, per_pass * L.r)) >= kWideCols;
         L.ld = (shared_rows && q >= 64) ? (int)round_up(q, 32) : q;
         L.x_off = off;
         off = round_up(off + (int64_t)p * L.ld, 32);
@@ -91,9 +92,8 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         P.message_floats += (size_t)L.r * ((size_t)p + q);
     }
     P.param_floats = (size_t)off;
-    for (int i = 0; i < n_workers; ++i)
-        for (int l = 0; l < n_layers; ++l)
-            if ((int64_t)P.incident[i].size() * P.layers[l].r > kMaxCols) return PG_ERR_ARG;
+    for (int l = 0; l < n_layers; ++l)
+        if (P.layers[l].r > kMaxCols) return PG_ERR_ARG;  // one edge's columns must fit one pass
 
     // ---- projection state: edge-major, then layer, r_l columns of q_l floats ----
     P.q_off.resize((size_t)n_edges * n_layers);
@@ -143,11 +143,13 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         Geo &g = geo[l];
         int nv = L.q / L.V;  // vector loads per row
         // The row blocking depends on the stacked column count; size for the best-connected worker.
-        int rc_max = compiled_cols(std::max<int>(1, (int)max_deg * L.r));
+        // (a worker with more than kMaxCols stacked columns takes several passes of whole edges)
+        const int per_pass = std::min<int>((int)max_deg, std::max(1, kMaxCols / L.r));
+        int rc_max = compiled_cols(std::max(1, per_pass * L.r));
         g.wide = rc_max >= kWideCols;
         // Row passes on the matrix cores pay from 16 stacked columns on (measured: at 8 the vector
         // kernels' P-sweep is the faster one) and address a layer with 32-bit byte offsets.
-        g.mrow = tune.mfma_rows && rc_max >= kMfmaRowCols && (int64_t)L.p * L.ld < ((int64_t)1 << 30);
+        g.mrow = tune.mfma_rows && rc_max >= tune.mfma_row_cols && (int64_t)L.p * L.ld < ((int64_t)1 << 30);
         // Lanes per row: a whole wavefront for few stacked columns; 16 for many, where the
         // per-row lane reduction (RC values per row) would otherwise rival the products.
         g.lpr = std::min((g.wide && !g.mrow) ? 16 : 64, pow2_ceil(nv));
@@ -213,43 +215,68 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     }
 
     // ---- (worker, layer) pairs with their stacked columns ----
-    P.pairs.resize((size_t)n_layers * n_workers);
+    // A worker multiplies its matrix by the columns of all its incident edges in one pass when
+    // they number at most kMaxCols; otherwise its edges are split into groups of whole edges,
+    // one PairDesc (one pass over the matrix) per group.
+    P.pairs.clear();
+    P.pair_first.assign((size_t)n_layers * n_workers, 0);
+    P.pair_count.assign((size_t)n_layers * n_workers, 0);
+    P.max_groups = 1;
     P.cols.clear();
     int64_t pwo = 0, qwo = 0;
+    // per (layer, worker, incident slot): which group the edge is in, and its first column there
+    std::vector<std::vector<std::pair<int, int>>> slot_home((size_t)n_layers * n_workers);
     for (int l = 0; l < n_layers; ++l) {
         const LayerInfo &L = P.layers[l];
         const Geo &g = geo[l];
+        const int epg = std::max(1, kMaxCols / L.r);  // edges per group
         for (int i = 0; i < n_workers; ++i) {
-            PairDesc &pd = P.pairs[(size_t)l * n_workers + i];
-            pd.worker = i;
-            pd.p = L.p;
-            pd.q = L.q;
-            pd.R = (int)P.incident[i].size() * L.r;
-            pd.x_off = L.x_off;
-            pd.pw_off = pwo;
-            pd.qw_off = qwo;
-            pd.col0 = (int)P.cols.size();
-            pd.lpr = g.lpr;
-            pd.nseg = g.nseg;
-            pd.seg_len = g.seg_len;
-            pd.lg = g.lg;
-            pd.nblk = g.nblk;
-            pd.blk_rows = g.blk_rows;
-            pd.V = L.V;
-            pd.wc = g.wc;
-            pd.ld = L.ld;
-            pwo += (int64_t)g.nseg * pd.R * L.p;
-            qwo += (int64_t)g.nblk * pd.R * L.q;
-            for (int e : P.incident[i])
-                for (int k = 0; k < L.r; ++k) {
-                    ColDesc c;
-                    size_t id = (size_t)e * n_layers + l;
-                    c.q_off = P.q_off[id] + (int64_t)k * L.q;
-                    c.ph_off = P.ph_off[id] + (int64_t)k * L.p;
-                    c.coef = (P.edges[2 * e] == i) ? P.edge_w[e] : -P.edge_w[e];
-                    c.pad = 0;
-                    P.cols.push_back(c);
+            const auto &inc = P.incident[i];
+            const size_t li = (size_t)l * n_workers + i;
+            const int ngroups = std::max<int>(1, ((int)inc.size() + epg - 1) / epg);
+            P.pair_first[li] = (int)P.pairs.size();
+            P.pair_count[li] = ngroups;
+            P.max_groups = std::max(P.max_groups, ngroups);
+            slot_home[li].resize(inc.size());
+            for (int gi = 0; gi < ngroups; ++gi) {
+                const int s0 = gi * epg, s1 = std::min<int>((int)inc.size(), s0 + epg);
+                PairDesc pd;
+                pd.worker = i;
+                pd.p = L.p;
+                pd.q = L.q;
+                pd.R = (s1 - s0) * L.r;
+                pd.x_off = L.x_off;
+                pd.pw_off = pwo;
+                pd.qw_off = qwo;
+                pd.col0 = (int)P.cols.size();
+                pd.lpr = g.lpr;
+                pd.nseg = g.nseg;
+                pd.seg_len = g.seg_len;
+                pd.lg = g.lg;
+                pd.nblk = g.nblk;
+                pd.blk_rows = g.blk_rows;
+                pd.V = L.V;
+                pd.wc = g.wc;
+                pd.ld = L.ld;
+                pwo += (int64_t)g.nseg * pd.R * L.p;
+                qwo += (int64_t)g.nblk * pd.R * L.q;
+                for (int sl = s0; sl < s1; ++sl) {
+                    const int e = inc[sl];
+                    slot_home[li][sl] = {(int)P.pairs.size(), (sl - s0) * L.r};
+                    for (int k = 0; k < L.r; ++k) {
+                        ColDesc c;
+                        size_t id = (size_t)e * n_layers + l;
+                        c.q_off = P.q_off[id] + (int64_t)k * L.q;
+                        c.ph_off = P.ph_off[id] + (int64_t)k * L.p;
+                        c.coef = (P.edges[2 * e] == i) ? P.edge_w[e] : -P.edge_w[e];
+                        c.pad = 0;
+                        P.cols.push_back(c);
+                    }
                 }
+                P.pairs.push_back(pd);
+                P.pair_group.push_back(gi);
+                P.pair_layer.push_back(l);
+            }
         }
     }
 
@@ -262,13 +289,15 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         for (int e = 0; e < n_edges; ++e) {
             EdgeLayerDesc &d = P.els[(size_t)l * n_edges + e];
             int a = P.edges[2 * e], b = P.edges[2 * e + 1];
-            const PairDesc &pa = P.pairs[(size_t)l * n_workers + a];
-            const PairDesc &pb = P.pairs[(size_t)l * n_workers + b];
-            auto slot = [&](int w) {
+            auto home = [&](int w) {
                 const auto &inc = P.incident[w];
-                return (int)(std::find(inc.begin(), inc.end(), e) - inc.begin());
+                const int sl = (int)(std::find(inc.begin(), inc.end(), e) - inc.begin());
+                return slot_home[(size_t)l * n_workers + w][sl];
             };
-            int ja = slot(a) * L.r, jb = slot(b) * L.r;
+            const std::pair<int, int> ha = home(a), hb = home(b);
+            const PairDesc &pa = P.pairs[ha.first];
+            const PairDesc &pb = P.pairs[hb.first];
+            const int ja = ha.second, jb = hb.second;
             size_t id = (size_t)e * n_layers + l;
             d.p = L.p;
             d.q = L.q;
@@ -331,12 +360,17 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     P.col_classes.clear();
     P.isolated_pairs.clear();
     P.isolated_elems = 0;
+    P.pass_elems = 0;
     // many stacked columns: one class (one kernel instantiation) per vector width
-    auto row_class = [&](int RC, int V, bool mfma) -> size_t {
+    // (tiles of different column groups of one matrix must not update it at the same time: every
+    // group index has launches of its own)
+    auto row_class = [&](int RC, int V, bool mfma, int group) -> size_t {
         if (RC < kWideCols) V = 0;
         for (size_t k = 0; k < P.row_classes.size(); ++k)
-            if (P.row_classes[k].RC == RC && P.row_classes[k].V == V && P.row_classes[k].mfma == mfma) return k;
-        P.row_classes.push_back({RC, V, mfma, {}, 0, 0, 0});
+            if (P.row_classes[k].RC == RC && P.row_classes[k].V == V && P.row_classes[k].mfma == mfma &&
+                P.row_classes[k].group == group)
+                return k;
+        P.row_classes.push_back({RC, V, mfma, {}, 0, 0, 0, group});
         return P.row_classes.size() - 1;
     };
     auto col_class = [&](int RC, int V) -> size_t {
@@ -349,8 +383,9 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     for (int l = 0; l < n_layers; ++l) {
         const LayerInfo &L = P.layers[l];
         const Geo &g = geo[l];
-        for (int i = 0; i < n_workers; ++i) {
-            int pair = l * n_workers + i;
+        for (int i = 0; i < n_workers; ++i)
+          for (int gi = 0; gi < P.pair_count[(size_t)l * n_workers + i]; ++gi) {
+            int pair = P.pair_first[(size_t)l * n_workers + i] + gi;
             const PairDesc &pd = P.pairs[pair];
             if (pd.R == 0) {  // isolated worker: nothing to multiply, no gossip term
                 P.isolated_pairs.push_back(pair);
@@ -359,7 +394,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             }
             int RC = compiled_cols(pd.R);
             const bool mrow = g.mrow && RC >= kWideCols;
-            RowClass &rc = P.row_classes[row_class(RC, L.V, mrow)];
+            RowClass &rc = P.row_classes[row_class(RC, L.V, mrow, gi)];
             int rows_iter = g.rows_iter_base * rows_unroll(RC);
             int tile_rows;
             if (RC < kWideCols) {
@@ -382,6 +417,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
                 for (int sg = 0; sg < g.nseg; ++sg)
                     rc.tiles.push_back({pair, r0, std::min(tile_rows, L.p - r0), sg});
             rc.elems += (double)L.p * L.q;
+            P.pass_elems += (double)L.p * L.q;
 
             ColClass &cc = P.col_classes[col_class(RC, L.V)];
             int cw = (RC >= kWideCols && tune.mfma_cols) ? kMfmaTileCols : g.lg * L.V;

@@ -27,6 +27,8 @@ struct RowClass {
     size_t dev_first = 0;   // index of the first tile in the uploaded table
     double elems = 0;       // parameter elements covered (for byte accounting)
     int max_seg = 0;        // RC >= kWideCols: longest column segment (sizes the Q slice in LDS)
+    int group = 0;          // which of a worker's column groups these tiles belong to (0 unless a worker
+                            // has more than kMaxCols stacked columns)
 };
 struct ColClass {
     int RC;
@@ -43,7 +45,8 @@ struct Tuning {
     int wide_tile_bytes = 256 * 1024; // target parameter bytes per wide row-owner tile (four wavefronts)
     // 8-16 stacked columns: which passes run on the matrix cores
     bool mfma_cols = true;            // Q-sweep
-    bool mfma_rows = true;            // P-sweep and update (layers with 16 stacked columns)
+    bool mfma_rows = true;            // P-sweep and update ...
+    int mfma_row_cols = kMfmaRowCols; // ... of layers with at least this many stacked columns (8 or 16)
 };
 
 struct Plan {
@@ -63,7 +66,11 @@ struct Plan {
     std::vector<int64_t> ph_off;             // [e * L + l] float offset inside the Phat section
     std::vector<int64_t> flag_off;           // [e * L + l] int32 index inside the flag section
 
-    std::vector<PairDesc> pairs;             // [l * n + i]
+    std::vector<PairDesc> pairs;             // one per (layer, worker, column group)
+    std::vector<int> pair_first, pair_count; // [l * n + i]: that worker's groups in `pairs`
+    std::vector<int> pair_group, pair_layer; // per pair: its group index and layer
+    int max_groups = 1;                      // most column groups any (worker, layer) has
+    double pass_elems = 0;                   // elements one sweep reads: sum of p * q over all pairs with edges
     std::vector<ColDesc> cols;
     std::vector<EdgeLayerDesc> els;          // [l * n_edges + e]
     std::vector<CombTile> comb_tiles;

@@ -97,26 +97,43 @@ static int check(const char *name, int n, const std::vector<int32_t> &e, const s
         return at == end;
     };
     int64_t pw_need = 0, qw_need = 0;
+    REQUIRE((int)P.pair_first.size() == L * n && (int)P.pair_count.size() == L * n, "pair index tables");
+    int next_pair = 0;
     for (int l = 0; l < L; ++l)
         for (int i = 0; i < n; ++i) {
-            const int pair = l * n + i;
-            const PairDesc &pd = P.pairs[pair];
-            REQUIRE(pd.p == rows[l] && pd.q == cols[l] && pd.worker == i, "pair %d fields", pair);
-            REQUIRE(pd.R == (int)P.incident[i].size() * P.layers[l].r, "R of pair %d", pair);
-            if (pd.R == 0) {
-                REQUIRE(!rcover.count({pair, 0}) && !ccover.count({pair, 0}), "tiles for a worker without edges");
-                continue;
+            const int first = P.pair_first[l * n + i], count = P.pair_count[l * n + i];
+            REQUIRE(first == next_pair && count >= 1 && count <= P.max_groups, "groups of layer %d worker %d", l, i);
+            next_pair += count;
+            int Rsum = 0;
+            for (int gi = 0; gi < count; ++gi) {
+                const int pair = first + gi;
+                const PairDesc &pd = P.pairs[pair];
+                REQUIRE(pd.p == rows[l] && pd.q == cols[l] && pd.worker == i, "pair %d fields", pair);
+                REQUIRE(P.pair_group[pair] == gi && P.pair_layer[pair] == l, "pair %d group/layer", pair);
+                REQUIRE(pd.R <= kMaxCols && pd.R % P.layers[l].r == 0, "R=%d of pair %d", pd.R, pair);
+                REQUIRE(pd.ld >= pd.q && (pd.ld == pd.q || pd.ld % 32 == 0), "row stride %d of pair %d", pd.ld, pair);
+                Rsum += pd.R;
+                if (pd.R == 0) {
+                    REQUIRE(count == 1, "empty group beside others");
+                    REQUIRE(!rcover.count({pair, 0}) && !ccover.count({pair, 0}), "tiles for a worker without edges");
+                    continue;
+                }
+                REQUIRE((int64_t)pd.nseg * pd.seg_len >= pd.q && (int64_t)(pd.nseg - 1) * pd.seg_len < pd.q, "segments of pair %d", pair);
+                REQUIRE((int64_t)pd.nblk * pd.blk_rows >= pd.p && (int64_t)(pd.nblk - 1) * pd.blk_rows < pd.p, "blocks of pair %d", pair);
+                for (int sg = 0; sg < pd.nseg; ++sg)
+                    REQUIRE(tiles_exactly(rcover[{pair, sg}], pd.p), "rows of pair %d (layer %d, worker %d), segment %d", pair, l, i, sg);
+                for (int b = 0; b < pd.nblk; ++b)
+                    REQUIRE(tiles_exactly(ccover[{pair, b}], pd.q), "columns of pair %d, block %d", pair, b);
+                REQUIRE(pd.pw_off == pw_need && pd.qw_off == qw_need, "partial-sum offsets of pair %d", pair);
+                pw_need += (int64_t)pd.nseg * pd.R * pd.p;
+                qw_need += (int64_t)pd.nblk * pd.R * pd.q;
             }
-            REQUIRE((int64_t)pd.nseg * pd.seg_len >= pd.q && (int64_t)(pd.nseg - 1) * pd.seg_len < pd.q, "segments of pair %d", pair);
-            REQUIRE((int64_t)pd.nblk * pd.blk_rows >= pd.p && (int64_t)(pd.nblk - 1) * pd.blk_rows < pd.p, "blocks of pair %d", pair);
-            for (int sg = 0; sg < pd.nseg; ++sg)
-                REQUIRE(tiles_exactly(rcover[{pair, sg}], pd.p), "rows of pair %d (layer %d, worker %d), segment %d", pair, l, i, sg);
-            for (int b = 0; b < pd.nblk; ++b)
-                REQUIRE(tiles_exactly(ccover[{pair, b}], pd.q), "columns of pair %d, block %d", pair, b);
-            REQUIRE(pd.pw_off == pw_need && pd.qw_off == qw_need, "partial-sum offsets of pair %d", pair);
-            pw_need += (int64_t)pd.nseg * pd.R * pd.p;
-            qw_need += (int64_t)pd.nblk * pd.R * pd.q;
+            REQUIRE(Rsum == (int)P.incident[i].size() * P.layers[l].r, "stacked columns of layer %d worker %d", l, i);
         }
+    REQUIRE(next_pair == (int)P.pairs.size(), "pair count");
+    // a row class holds tiles of one column group only (groups of one matrix never share a launch)
+    for (const RowClass &c : P.row_classes)
+        for (const RowTile &t : c.tiles) REQUIRE(P.pair_group[t.pair] == c.group, "tile of group %d in class of group %d", P.pair_group[t.pair], c.group);
     REQUIRE(P.ws_qw >= P.ws_pw + (size_t)pw_need * 8, "P partial sums do not fit their section");
     REQUIRE(P.ws_pd >= P.ws_qw + (size_t)qw_need * 8, "Q partial sums do not fit their section");
     REQUIRE(P.ws_bytes >= P.ws_uq, "workspace size");
@@ -163,6 +180,10 @@ int main() {
         e.clear();
         torus(3, 3, e);
         bad |= check("torus 3x3 rank 2", 9, e, std::vector<float>(18, 0.2f), {120, 33, 40, 2600}, {260, 12, 1, 63}, 2, 1, tn);
+        // more than 16 stacked columns: rank 8 (two groups of two edges), rank 6 (two of two), rank 16 (four of one)
+        bad |= check("torus 3x3 rank 8", 9, e, std::vector<float>(18, 0.2f), {120, 33, 40, 8, 700}, {260, 12, 1, 100, 650}, 8, 2, tn);
+        bad |= check("torus 3x3 rank 6", 9, e, std::vector<float>(18, 0.2f), {120, 33, 5}, {260, 12, 64}, 6, 1, tn);
+        bad |= check("torus 3x3 rank 16", 9, e, std::vector<float>(18, 0.2f), {120, 16, 40}, {260, 300, 1}, 16, 1, tn);
     }
     return bad;
 }

@@ -59,7 +59,7 @@ def test_bad_arguments_are_rejected():
         (lambda: _init(3, ok_edges, -0.1, [(4, 4)]), B.PG_ERR_ARG),
         (lambda: _init(3, ok_edges, float("nan"), [(4, 4)]), B.PG_ERR_ARG),
         (lambda: _init(3, ok_edges, 0.6, [(4, 4)]), B.PG_ERR_ARG),      # worker 1: 1.2 > 1
-        (lambda: _init(3, ok_edges, 0.2, [(64, 64)], rank=9), B.PG_ERR_ARG),  # 2 edges * 9 > 16 columns
+        (lambda: _init(3, ok_edges, 0.2, [(64, 64)], rank=17), B.PG_ERR_ARG),  # one edge's columns exceed a pass
     ]
     for fn, code in cases:
         with pytest.raises(B.PGError) as e:
@@ -226,7 +226,7 @@ def test_planner_tiles_cover_every_matrix_exactly_once(tmp_path):
     assert build.returncode == 0, build.stderr[-3000:]
     run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
     assert run.returncode == 0, run.stdout[-3000:]
-    assert run.stdout.count("ok ") == 21 and "FAIL" not in run.stdout
+    assert run.stdout.count("ok ") == 30 and "FAIL" not in run.stdout
 
 
 SAN = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-g"]
@@ -251,7 +251,7 @@ def test_planner_under_address_and_undefined_behaviour_sanitizers(tmp_path):
     src = [os.path.join(ROOT, "tests", "plan_cover.cpp"),
            os.path.join(ROOT, "paper_2008_01425_amd", "csrc", "pg_plan.cpp")]
     out = _run_sanitized(["g++", "-O1", "-std=c++17"] + SAN + ["-o", exe] + src, exe)
-    assert "FAIL" not in out and out.count("ok ") == 21
+    assert "FAIL" not in out and out.count("ok ") == 30
 
 
 @pytest.mark.parametrize("define", [[], ["-DPGO_ALL_DOUBLE"]])

@@ -567,7 +567,16 @@ __device__ __forceinline__ void wave_lds_sync() {
 // all 64 columns of a wavefront whose rows all exist run a body without any bounds handling.
 // RCM = compiled stacked columns / 4 (2 or 4): the instructions one update block takes per t.
 constexpr int kMrowXStride = 68;  // floats per LDS row: 64 + 4 keeps 128-bit reads down a column of lanes conflict-free
-constexpr int kMrowWaveFloats = 2 * 16 * kMrowXStride + 16 * 64;  // two X buffers and the Q slice of a step
+// The Q slice of a step, [column / 4][j][4]: 64 floats per group of four columns plus a pad that
+// spreads the lanes' staging writes over the banks (measured with a plain 64-float stride: 60 % of
+// the LDS cycles of the sweep were bank conflicts, all 64 lanes of a write landing on 16 banks).
+// 8-byte writes (rows of even length) want a shift of 8 banks per group, the others 4.
+constexpr int kMrowQStrideMax = 72;
+template <int V>
+struct MrowQStride {
+    static constexpr int value = V == 2 ? 72 : 68;
+};
+constexpr int kMrowWaveFloats = 2 * 16 * kMrowXStride + 16 * kMrowQStrideMax;  // two X buffers and the Q slice of a step
 constexpr size_t kMrowLdsBytes = (size_t)(kThreads / 64) * kMrowWaveFloats * sizeof(float);
 template <bool B>
 struct BoolTag {
@@ -680,7 +689,7 @@ mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse, const Pa
                     for (int e = 0; e < V; ++e)
                         tv[e] = UPDATE ? f.qu[UPDATE ? (i < RCM ? i : RCM - 1) : 0][V * u + e]
                                        : f.qs[(SWEEP && !UPDATE) ? i : 0][V * u + e];
-                    *reinterpret_cast<typename VecT<V>::T *>(qbuf + ((c >> 2) * 16 + hi + 4 * i) * 4 + (c & 3)) = tv;
+                    *reinterpret_cast<typename VecT<V>::T *>(qbuf + (c >> 2) * MrowQStride<V>::value + (hi + 4 * i) * 4 + (c & 3)) = tv;
                 }
             }
             wave_lds_sync();
@@ -729,7 +738,7 @@ mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse, const Pa
                 for (int s2 = 0; s2 < 4; ++s2) {
                     const VecT<4>::T av =
                         *reinterpret_cast<const VecT<4>::T *>(xb + lo * kMrowXStride + 16 * s2 + 4 * hi);
-                    const VecT<4>::T bv = *reinterpret_cast<const VecT<4>::T *>(qbuf + ((4 * s2 + hi) * 16 + lo) * 4);
+                    const VecT<4>::T bv = *reinterpret_cast<const VecT<4>::T *>(qbuf + (4 * s2 + hi) * MrowQStride<V>::value + lo * 4);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) acc[b] = mfma16((double)av[e], (double)bv[e], acc[b]);
                     PG_FENCE();

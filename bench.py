@@ -225,6 +225,20 @@ def main():
         it[0] += 1
     stats_it = event_times(one_iteration, 2 * Kp, 1)
 
+    # ---- the P-sweep without its predecessor's write-backs: between two pg_round calls read 1 GiB
+    # of other memory, which evicts the dirty lines the update pass left in the memory-side cache
+    # (that read pays for their write-back instead of the sweep)
+    other = torch.ones((1 << 30) // 4, dtype=torch.float32, device="cuda")
+
+    def rounds_with_eviction():
+        for _ in range(10):
+            other.sum()
+            gb.round()
+    rounds_with_eviction()
+    k_evicted = kernel_table(B, gb, rounds_with_eviction)
+    del other
+    torch.cuda.empty_cache()
+
     traffic, traffic_src = traffic_from_profiles(wl.name)
     # the dominant kernel of the timed (fused) pipeline
     dom = max(k_fused.items(), key=lambda kv: kv[1]["total_ms"])
@@ -243,6 +257,11 @@ def main():
                                          "runs_after": "the P-sweep (a read-only pass)"},
         "sweep_q_in_pg_run": sq_f and {"GBps": sq_f["GBps"], "frac": sq_f["frac_of_peak"], "avg_ms": sq_f["avg_ms"],
                                        "runs_after": "the fused update + P-sweep (a pass that wrote every parameter)"},
+        "sweep_p_in_pg_round_after_evicting_read": k_evicted.get("sweep_p") and {
+            "GBps": k_evicted["sweep_p"]["GBps"], "frac": k_evicted["sweep_p"]["frac_of_peak"],
+            "avg_ms": k_evicted["sweep_p"]["avg_ms"],
+            "runs_after": "a 1 GiB read of other memory placed behind the update (it evicts the update's dirty "
+                          "lines from the memory-side cache and pays for their write-back)"},
         "target_frac": TARGET_FRAC,
     }
     fr = [v["frac"] for k, v in sweeps.items() if isinstance(v, dict)]

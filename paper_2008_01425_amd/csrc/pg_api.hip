@@ -478,7 +478,11 @@ int pg_init(pg_ctx **out, int n_workers, int n_edges, const int32_t *edges, cons
     if (const char *e = getenv("PG_ROW_TILE_BYTES")) tune.row_tile_bytes = std::max(1024, atoi(e));
     if (const char *e = getenv("PG_ALTERNATE")) c->alternate = atoi(e) != 0;
     if (const char *e = getenv("PG_COL_TILE_BYTES")) tune.col_tile_bytes = std::max(1024, atoi(e));
-    if (const char *e = getenv("PG_WIDE_TILE_BYTES")) tune.wide_tile_bytes = std::max(1024, atoi(e));
+    if (const char *e = getenv("PG_WIDE_TILE_BYTES")) {
+        tune.wide_tile_bytes = std::max(1024, atoi(e));
+        tune.mcol_tile_bytes = 2 * tune.wide_tile_bytes;
+    }
+    if (const char *e = getenv("PG_MCOL_TILE_BYTES")) tune.mcol_tile_bytes = std::max(1024, atoi(e));
     if (const char *e = getenv("PG_MFMA_ROWS")) tune.mfma_rows = atoi(e) != 0;
     if (const char *e = getenv("PG_MFMA_COLS")) tune.mfma_cols = atoi(e) != 0;
     if (const char *e = getenv("PG_MFMA_ROW_COLS")) tune.mfma_row_cols = atoi(e) <= 8 ? 8 : 16;

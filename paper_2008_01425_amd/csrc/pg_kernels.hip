@@ -260,6 +260,67 @@ __device__ __forceinline__ void row_body(const RowTile &t, const PairDesc &pd,
     }
 }
 
+// The same pass for a vector layer (p x 1: a bias, a normalisation scale).  Its "rows" are single
+// floats next to each other in memory, so lanes take consecutive rows (coalesced) instead of one
+// lane group per row; every product is a scalar multiple, with the same operations in the same
+// order as the general body performs for q = 1.
+template <int RC, bool UPDATE, bool SWEEP, bool GRAD>
+__device__ __forceinline__ void vec_row_body(const RowTile &t, const PairDesc &pd,
+                                             const ColDesc *__restrict__ cols, float *X,
+                                             const float *__restrict__ qstate,
+                                             const float *__restrict__ phat, double *__restrict__ pw,
+                                             const float *Gp, double eta) {
+    constexpr int U = 4;  // rows in flight per lane
+    const int R = pd.R;
+    const int row_end = t.row0 + t.nrows;
+    double qd[RC];
+    const float *phc[RC];
+    float coef[RC];
+#pragma unroll
+    for (int j = 0; j < RC; ++j) {
+        const ColDesc cd = cols[pd.col0 + min(j, R - 1)];
+        qd[j] = (double)ldg1(qstate + cd.q_off);
+        phc[j] = phat + cd.ph_off;
+        coef[j] = (j < R) ? cd.coef : 0.0f;
+    }
+    for (int base = t.row0 + (int)threadIdx.x; base < row_end; base += 64 * U) {
+        int row[U];
+        bool ok[U];
+        double x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            ok[u] = base + 64 * u < row_end;
+            row[u] = ok[u] ? base + 64 * u : row_end - 1;
+            x[u] = (double)ldg1(X + row[u]);
+        }
+        if (UPDATE) {
+            float ph[U][RC], g[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int j = 0; j < RC; ++j) ph[u][j] = ldg1(phc[j] + row[u]);
+                g[u] = GRAD ? ldg1(Gp + row[u]) : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int j = 0; j < RC; ++j) x[u] = fma(-((double)coef[j] * (double)ph[u][j]), qd[j], x[u]);
+                if (GRAD) x[u] = fma(-eta, (double)g[u], x[u]);
+                const float xf = (float)x[u];
+                if (ok[u]) *(PG_GLOBAL float *)(X + row[u]) = xf;
+                x[u] = (double)xf;  // the sweep uses the stored (rounded) value
+            }
+        }
+        if (SWEEP) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int j = 0; j < RC; ++j)
+                    if (ok[u] && j < R) pw[pd.pw_off + (int64_t)j * pd.p + row[u]] = fma(x[u], qd[j], 0.0);
+        }
+    }
+}
+
 // One wavefront per tile; `reverse` walks the tile list backwards so that a pass can start on
 // the data the previous pass touched last (still resident in the memory-side cache).
 //   GRAD  : (with UPDATE) also subtract eta * G[row, c]: the update step of Algorithm 1 in one pass.
@@ -274,7 +335,8 @@ row_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
     const PairDesc pd = pairs[t.pair];
     float *X = xs[pd.worker] + pd.x_off;
     const float *Gp = GRAD ? gs[pd.worker] + pd.x_off : nullptr;
-    if (pd.V == 4) row_body<4, RC, M, D, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
+    if (pd.q == 1) vec_row_body<RC, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
+    else if (pd.V == 4) row_body<4, RC, M, D, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
     else if (pd.V == 2) row_body<2, RC, M, D, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
     else row_body<1, RC, M, D, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
 }

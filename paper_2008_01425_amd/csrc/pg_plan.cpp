@@ -126,6 +126,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         tn.row_tile_bytes = (int)std::max(8.0 * 1024, std::min((double)tune.row_tile_bytes, total_bytes / slots));
         tn.col_tile_bytes = (int)std::max(32.0 * 1024, std::min((double)tune.col_tile_bytes, 4.0 * total_bytes / slots));
         tn.wide_tile_bytes = (int)std::max(32.0 * 1024, std::min((double)tune.wide_tile_bytes, 4.0 * total_bytes / slots));
+        tn.mcol_tile_bytes = (int)std::max(64.0 * 1024, std::min((double)tune.mcol_tile_bytes, 8.0 * total_bytes / slots));
     }
 
     // ---- per-layer launch geometry ----
@@ -205,7 +206,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         int64_t unit = (int64_t)row_groups * kColUnroll;
         if (g.wide && tune.mfma_cols) {
             // four wavefronts per tile of kMfmaTileCols columns
-            want = std::max<int64_t>(16, tn.wide_tile_bytes * 2 / (kMfmaTileCols * 4));
+            want = std::max<int64_t>(16, tn.mcol_tile_bytes / (kMfmaTileCols * 4));
             unit = 16;
         }
         int64_t br = round_up(want, unit);

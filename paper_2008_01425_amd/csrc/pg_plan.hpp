@@ -43,6 +43,7 @@ struct Tuning {
     int row_tile_bytes = 72 * 1024;  // target parameter bytes per row-owner tile (one wavefront)
     int col_tile_bytes = 512 * 1024; // target parameter bytes per column-owner tile (four wavefronts)
     int wide_tile_bytes = 256 * 1024; // target parameter bytes per wide row-owner tile (four wavefronts)
+    int mcol_tile_bytes = 512 * 1024; // target parameter bytes per matrix-core column tile (256 columns x a row block)
     // 8-16 stacked columns: which passes run on the matrix cores
     bool mfma_cols = true;            // Q-sweep
     bool mfma_rows = true;            // P-sweep and update ...

@@ -185,6 +185,21 @@ def test_seeded_blocks_are_reproducible_and_independent():
     assert q.shape == (1, 32) and abs(q.std() - 1.0) < 0.3
 
 
+def test_planted_spectrum_gives_every_edge_the_prescribed_singular_values():
+    """Workload.spectrum: worker i adds (i + 1) * sum_k sigma_k u_k v_k^T with shared orthonormal
+    directions, so the difference of workers a and b has singular values |a - b| * sigma_k above
+    the noise floor, in the planted ratios on every edge."""
+    spectrum = (200.0, 2.0, 1.0, 0.5)
+    wl = W.Workload("planted", 5, W.ring_edges(5), np.full((5,), 0.05, np.float32), [(60, 80), (33, 1)],
+                    4, 1, 1e-6, 10, 11, spectrum)
+    X = wl.all_params()
+    for a, b in ((0, 1), (3, 4), (4, 0)):
+        sv = np.linalg.svd(X[a][0].astype(np.float64) - X[b][0].astype(np.float64), compute_uv=False)
+        assert np.allclose(sv[:4], abs(a - b) * np.array(spectrum), rtol=1e-3)
+        assert sv[4] < 1e-3 * sv[3]
+    assert X[0][1].shape == (33, 1) and np.array_equal(X[0][0], wl.worker_layer(0, 0))
+
+
 def test_one_hip_runtime_whichever_of_library_and_torch_loads_first():
     """The library must share torch's HIP runtime also when it is loaded before torch (host-only
     tests collected ahead of GPU tests do exactly that); two runtimes in one process leave the

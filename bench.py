@@ -62,6 +62,20 @@ def cpu_baseline(wl, seconds_budget: float):
                       f"{dt:.1f} s on one host core ({os.cpu_count()} visible)"}
 
 
+def consensus_distance(gb) -> float:
+    """(1/n) sum_i |X_i - mean|_F^2 over all layers (the objective of the paper's consensus
+    experiment): a read-out for the JSON line, not part of the path."""
+    import torch
+    mean = torch.zeros_like(gb.x[0], dtype=torch.float64)
+    for x in gb.x:
+        mean += x
+    mean /= gb.n
+    total = 0.0
+    for x in gb.x:
+        total += float(((x.double() - mean) ** 2).sum())
+    return total / gb.n
+
+
 def event_times(fn, reps: int, per_call: int):
     """ms per round of `reps` calls of fn (each `per_call` rounds), timed with HIP events on the
     stream the library launches on (torch's current stream)."""
@@ -169,6 +183,7 @@ def main():
     gb = GossipBuffers.from_workload(wl)
     K, Wm = args.steps, args.warmup
 
+    dist0 = consensus_distance(gb) if args.counters == 0 else None
     # ---- timed region: K consecutive rounds, fused pipeline -------------------------------
     if Wm > 0:
         gb.run(Wm)
@@ -195,6 +210,7 @@ def main():
         gb.close()
         return
 
+    dist1 = consensus_distance(gb)
     # the same pipeline again as 5 event-timed calls (spread of the per-round time)
     stats_fused = event_times(lambda: gb.run(K), 5, K)
     # ---- the same rounds as isolated pg_round calls (no cross-round fusion) ---------------
@@ -289,6 +305,8 @@ def main():
                    "rank": wl.rank, "power_steps": wl.power_steps,
                    "storage": "f32", "accumulate": "f64", "pipeline": "pg_run (fused update + next sweep)"},
         "ms_per_step_events": stats_fused,
+        "consensus_distance": {"start": dist0, f"after_{Wm + K}_rounds": dist1,
+                               "what": "(1/n) sum_i |X_i - mean|^2 over all layers"},
         "round_GBps": bytes_fused / (ms_per_step * 1e-3) / 1e9,
         "round_frac_of_peak": bytes_fused / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "bytes_per_param_per_round": bytes_fused / nparam,

@@ -47,7 +47,8 @@ def test_static_workspace_round_matches_pg_round_twice_in_a_row_second_call_smal
     a1.round_static()               # first call
     a2.round_static()               # second call, smaller input, same workspace
     torch.cuda.synchronize()
-    assert torch.cuda.mem_get_info()[0] >= free_before, "device memory was allocated inside pg_round_static"
+    # (a workspace of this problem would be 25 MiB; 2 MiB of slack for the runtime's own housekeeping)
+    assert torch.cuda.mem_get_info()[0] >= free_before - (2 << 20), "device memory was allocated inside pg_round_static"
     _same(a1, b1, "first call")
     _same(a2, b2, "second, smaller call")
     print("case static interleaved", flush=True)

@@ -270,7 +270,7 @@ struct Launcher {
         const Plan &P = c->plan;
         if (status || P.isolated_pairs.empty()) return;
         begin(K_UPDATE_SGD, P.isolated_elems * 12.0);
-        sgd_only_kernel<<<dim3(64, (unsigned)P.isolated_pairs.size()), dim3(kThreads), 0, st>>>(
+        sgd_only_kernel<<<dim3(64u * (unsigned)P.isolated_pairs.size()), dim3(kThreads), 0, st>>>(
             c->d_iso, c->d_pairs, c->d_xs, c->d_gs, eta);
         check();
         end();

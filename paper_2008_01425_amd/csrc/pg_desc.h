@@ -14,6 +14,7 @@ constexpr int kThreads = 256;  // work-group size of the column-owner and combin
 constexpr int kRowThreads = 64;  // narrow row-owner kernels: one wavefront per tile
 constexpr int kWideCols = 8;     // from this many compiled columns on, row tiles stage Q in LDS
 constexpr int kWideLdsBytes = 48 * 1024;  // LDS budget of a wide row tile's Q slice
+constexpr int kColLdsBytes = 48 * 1024;   // LDS budget of a (vector) column tile's Phat slice
 constexpr int kMfmaRowBlocks = 2;  // matrix-core row tiles: blocks of 16 rows per wavefront
 constexpr int kMfmaRowCols = 16;    // stacked columns from which row passes run on the matrix cores
 constexpr int kMfmaSegCols = 2048;  // matrix-core row tiles: longest column segment

@@ -1002,12 +1002,13 @@ mcol_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
 __global__ void __launch_bounds__(kThreads)
 sgd_only_kernel(const int32_t *__restrict__ pair_ids, const PairDesc *__restrict__ pairs,
                 float *const *__restrict__ xs, const float *const *__restrict__ gs, double eta) {
-    const PairDesc pd = pairs[pair_ids[blockIdx.y]];
+    // 64 work-groups per listed pair (a one-dimensional grid: the list may be longer than a grid's y range)
+    const PairDesc pd = pairs[pair_ids[blockIdx.x >> 6]];
     float *X = xs[pd.worker] + pd.x_off;
     const float *G = gs[pd.worker] + pd.x_off;
     const int64_t total = (int64_t)pd.p * pd.q;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total;
-         i += (int64_t)gridDim.x * kThreads) {
+    for (int64_t i = (int64_t)(blockIdx.x & 63) * kThreads + threadIdx.x; i < total;
+         i += (int64_t)64 * kThreads) {
         const int64_t at = (i / pd.q) * pd.ld + i % pd.q;
         X[at] = (float)fma(-eta, (double)G[at], (double)X[at]);
     }

@@ -210,6 +210,11 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             unit = 16;
         }
         int64_t br = round_up(want, unit);
+        if (!(g.wide && tune.mfma_cols)) {
+            // the vector column kernel stages the block's Phat slice in LDS: (rows + 1) x columns floats
+            const int64_t cap = kColLdsBytes / (4 * rc_max) - 1;
+            if (br > cap) br = cap >= unit ? cap / unit * unit : cap;
+        }
         if (br >= L.p) br = L.p;
         g.blk_rows = (int)br;
         g.nblk = (L.p + g.blk_rows - 1) / g.blk_rows;

@@ -84,7 +84,10 @@ static int check(const char *name, int n, const std::vector<int32_t> &e, const s
             REQUIRE(t.blk >= 0 && t.blk < pd.nblk && (int64_t)t.blk * pd.blk_rows < pd.p, "row block %d", t.blk);
             const int cw = (c.RC >= kWideCols && P.mfma_cols) ? kMfmaTileCols : pd.lg * pd.V;
             REQUIRE(t.c0 >= 0 && t.c0 < pd.q && t.c0 % cw == 0, "column tile at %d, width %d", t.c0, cw);
-            if (!(c.RC >= kWideCols && P.mfma_cols)) REQUIRE(c.max_rows >= pd.blk_rows, "max_rows");
+            if (!(c.RC >= kWideCols && P.mfma_cols)) {
+                REQUIRE(c.max_rows >= pd.blk_rows, "max_rows");
+                REQUIRE((int64_t)(pd.blk_rows + 1) * c.RC * 4 <= kColLdsBytes, "Phat slice of %d rows x %d columns", pd.blk_rows, c.RC);
+            }
             ccover[{t.pair, t.blk}].push_back({t.c0, std::min(pd.q, t.c0 + cw)});
         }
     auto tiles_exactly = [](std::vector<std::pair<int, int>> v, int end) {
@@ -180,6 +183,8 @@ int main() {
         e.clear();
         torus(3, 3, e);
         bad |= check("torus 3x3 rank 2", 9, e, std::vector<float>(18, 0.2f), {120, 33, 40, 2600}, {260, 12, 1, 63}, 2, 1, tn);
+        bad |= check("extreme aspect ratios", 9, e, std::vector<float>(18, 0.2f), {5, 300001, 1, 2, 70001, 33278},
+                     {100003, 3, 1, 65537, 1, 1}, 4, 1, tn);
         // more than 16 stacked columns: rank 8 (two groups of two edges), rank 6 (two of two), rank 16 (four of one)
         bad |= check("torus 3x3 rank 8", 9, e, std::vector<float>(18, 0.2f), {120, 33, 40, 8, 700}, {260, 12, 1, 100, 650}, 8, 2, tn);
         bad |= check("torus 3x3 rank 6", 9, e, std::vector<float>(18, 0.2f), {120, 33, 5}, {260, 12, 64}, 6, 1, tn);

@@ -677,6 +677,67 @@ def test_single_iterations_on_degenerate_differences():
     gb.close()
 
 
+# ------------------------------------------------------------------ extreme aspect ratios
+@pytest.mark.parametrize("topo,rank", [("ring", 2), ("torus", 4)])
+def test_very_wide_very_tall_and_one_by_one_layers(topo, rank):
+    """Rows of 100003 floats (many column segments, odd length), 300001 rows of 3 (many row tiles
+    and orthonormalisation chunks), a 1 x 1 layer, two rows of 65537: on the narrow kernels (ring)
+    and on the 16-column ones (torus)."""
+    n, edges, w = (3, W.ring_edges(3), 1 / 3) if topo == "ring" else (9, W.torus_edges(3, 3), 1 / 5)
+    shapes = [(5, 100003), (300001, 3), (1, 1), (2, 65537), (70001, 1)]
+    wl = _custom(f"aspect_{topo}", n, edges, w, shapes, rank, 1)
+    _check(wl, 1, TOL_1)
+    _check(wl, 2, TOL_10, fused=True)
+
+
+# ------------------------------------------------------------------ maximum sizes
+def test_one_layer_of_two_to_the_thirty_elements():
+    """A 32768 x 32768 layer: 4 GiB per worker, byte offsets past 2^32 inside one matrix, 64-bit row
+    arithmetic in every pass, partial sums of 32768 rows and columns.  Two workers, one edge,
+    rank 1, one round and a fused second one; inputs are a random 2048 x 32768 block repeated
+    (drawing 3 x 2^30 normals would take longer than the rest of the test)."""
+    from paper_2008_01425_amd.device import GossipBuffers
+    from oracle import pg_oracle as O
+    p = q = 32768
+    rng = np.random.default_rng(77)
+    t0 = time.time()
+    reps = p // 2048
+
+    def big(scale, shift):
+        blk = rng.standard_normal((2048, q), dtype=np.float32) * np.float32(scale)
+        a = np.tile(blk, (reps, 1))
+        # make the repeats differ: a smooth factor per row block
+        a *= (1.0 + shift * np.repeat(np.arange(reps, dtype=np.float32), 2048))[:, None]
+        return a
+    base = big(1.0, 0.01)
+    Xa = base + big(0.01, 0.03)
+    Xb = base + big(0.01, 0.05)
+    del base
+    Q0 = rng.standard_normal((1, q)).astype(np.float32)
+    print(f"case 2^30 elements: inputs {time.time() - t0:.0f} s", flush=True)
+    gb = GossipBuffers(2, [[0, 1]], [0.4], [(p, q)], 1, 1)
+    assert gb.N == p * q
+    gb.set_layer(0, 0, Xa); gb.set_layer(1, 0, Xb); gb.set_q(0, 0, Q0)
+    gb.run(2)
+    print(f"   GPU rounds queued {time.time() - t0:.0f} s", flush=True)
+    prob = O.Problem(2, np.array([[0, 1]]), np.array([np.float64(np.float32(0.4))]), [(p, q)], 1, 1)
+    X, Q = [[Xa], [Xb]], [[Q0]]
+    for t in range(2):
+        info = O.gossip_round(prob, X, Q, want_phat=True)
+        print(f"   oracle round {t + 1} {time.time() - t0:.0f} s", flush=True)
+    for i in range(2):
+        got = gb.get_layer(i, 0)
+        # strided check of the whole matrix plus its last rows and columns, element by element
+        for sl in (np.s_[::7, ::5], np.s_[-64:, :], np.s_[:, -64:]):
+            assert rel_err(got[sl], X[i][0][sl]) <= TOL_1, (i, sl)
+        del got
+    assert rel_err(gb.get_q(0, 0), Q[0][0]) <= TOL_1
+    assert rel_err(gb.get_phat(0, 0), info.phat[0][0]) <= TOL_1
+    assert np.array_equal(gb.get_flags(0, 0), info.degenerate[0][0])
+    print(f"   done {time.time() - t0:.0f} s", flush=True)
+    gb.close()
+
+
 # ------------------------------------------------------------------ full-size configurations
 # Every named configuration, every layer, one and ten rounds, through pg_round and through pg_run
 # (tiny and resnet20 above; the oracle's ten rounds take seconds for the VGG-16 shapes, about

@@ -196,8 +196,12 @@ struct Launcher {
         const int n = (int)rc.tiles.size();
         const RowTile *tiles = c->d_row_tiles + rc.dev_first;
         if constexpr (RC < kWideCols) {
-            row_kernel<RC, kRowsPerGroup, kPrefetchSteps, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
-                tiles, n, c->reverse, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
+            if (rc.vec)
+                vec_row_kernel<RC, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
+                    tiles, n, c->reverse, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
+            else
+                row_kernel<RC, kRowsPerGroup, kPrefetchSteps, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
+                    tiles, n, c->reverse, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
         } else if (rc.mfma) {
 #define PG_MROW(VV) mrow_kernel<VV, RC / 4, kMfmaRowBlocks, kMfmaRowPrefetch, UPD, SWP, GRAD> \
                 <<<dim3((unsigned)n), dim3(kThreads), kMrowLdsBytes, st>>>( \
@@ -278,7 +282,7 @@ struct Launcher {
 
     template <int RC>
     void col_launch(const ColClass &cc) {
-        constexpr int U = (RC <= 2) ? 8 : 4;  // rows in flight per lane
+        constexpr int U = (RC <= 4) ? 8 : 4;  // rows in flight per lane
         const int n = (int)cc.tiles.size();
         // LDS: the staged Phat slice plus one zero row, later reused for the cross-wavefront sums
         size_t lds = std::max((size_t)(cc.max_rows + 1) * RC * sizeof(float),
@@ -287,7 +291,11 @@ struct Launcher {
             c->d_col_tiles + cc.dev_first, n, c->reverse, c->d_pairs, c->d_cols, \
             c->d_xs, left(), qw())
         if constexpr (RC < kWideCols) {
-            PG_COL(0);
+            if (cc.vec)
+                vec_col_kernel<RC><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
+                    c->d_col_tiles + cc.dev_first, n, c->reverse, c->d_pairs, c->d_cols, c->d_xs, left(), qw());
+            else
+                PG_COL(0);
         } else if (c->plan.mfma_cols) {
 #define PG_MCOL(VV) mcol_kernel<VV, kMfmaColPrefetch><<<dim3((unsigned)n), dim3(kThreads), 0, st>>>( \
             c->d_col_tiles + cc.dev_first, n, c->reverse, c->d_pairs, c->d_cols, \
@@ -485,6 +493,7 @@ int pg_init(pg_ctx **out, int n_workers, int n_edges, const int32_t *edges, cons
     if (const char *e = getenv("PG_MCOL_TILE_BYTES")) tune.mcol_tile_bytes = std::max(1024, atoi(e));
     if (const char *e = getenv("PG_MFMA_ROWS")) tune.mfma_rows = atoi(e) != 0;
     if (const char *e = getenv("PG_MFMA_COLS")) tune.mfma_cols = atoi(e) != 0;
+    if (const char *e = getenv("PG_VEC_KERNELS")) tune.vec_kernels = std::min(2, std::max(0, atoi(e)));
     if (const char *e = getenv("PG_MFMA_ROW_COLS")) tune.mfma_row_cols = atoi(e) <= 8 ? 8 : 16;
     int rc;
     try {

@@ -341,6 +341,23 @@ row_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
     else row_body<1, RC, M, D, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
 }
 
+// The row passes over vector layers alone (one wavefront per tile): the same arithmetic as the
+// vector branch above in a kernel that needs few registers, so that many short tiles are
+// resident at once.
+template <int RC, bool UPDATE, bool SWEEP, bool GRAD>
+__global__ void __launch_bounds__(kRowThreads)
+vec_row_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse,
+               const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
+               float *const *__restrict__ xs, const float *__restrict__ qstate,
+               const float *__restrict__ phat, double *__restrict__ pw,
+               const float *const *__restrict__ gs, double eta) {
+    const RowTile t = tiles[tile_index(ntiles, reverse)];
+    const PairDesc pd = pairs[t.pair];
+    float *X = xs[pd.worker] + pd.x_off;
+    const float *Gp = GRAD ? gs[pd.worker] + pd.x_off : nullptr;
+    vec_row_body<RC, UPDATE, SWEEP, GRAD>(t, pd, cols, X, qstate, phat, pw, Gp, eta);
+}
+
 // ---------------------------------------------------------------------------------------
 // Row-owner kernel for many stacked columns (RC >= 8): four wavefronts per tile share the
 // tile's Q slice, staged once in LDS (RC x segment floats), so each loaded X value meets all
@@ -1045,11 +1062,12 @@ __device__ __forceinline__ void col_body(const ColTile &t, const PairDesc &pd,
 
     // stage Phat[rb:re, 0:R) as sT[row][j]; columns j >= R and the extra row `nrows` are zero
     // (rows past the block's end are pointed at that zero row)
-#pragma unroll 1
-    for (int j = 0; j < RC; ++j) {
-        const float *src = (j < R) ? phat + cols[pd.col0 + j].ph_off + rb : nullptr;
-        for (int rr = threadIdx.x; rr <= nrows; rr += kThreads)
-            sT[rr * RC + j] = (j < R && rr < nrows) ? ldg1(src + rr) : 0.0f;
+    const float *src[RC];
+#pragma unroll
+    for (int j = 0; j < RC; ++j) src[j] = phat + cols[pd.col0 + min(j, R - 1)].ph_off + rb;
+    for (int rr = threadIdx.x; rr <= nrows; rr += kThreads) {
+#pragma unroll
+        for (int j = 0; j < RC; ++j) sT[rr * RC + j] = (j < R && rr < nrows) ? ldg1(src[j] + rr) : 0.0f;
     }
 
     double acc[RC][V];
@@ -1151,6 +1169,53 @@ col_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
         if (pd.V == 4) col_body<4, RC, U>(t, pd, cols, X, phat, qw, sT);
         else if (pd.V == 2) col_body<2, RC, U>(t, pd, cols, X, phat, qw, sT);
         else col_body<1, RC, U>(t, pd, cols, X, phat, qw, sT);
+    }
+}
+
+// The Q-sweep of vector layers alone: X_i^T Phat_j is a dot product per stacked column.  One
+// wavefront per (worker, layer, row block), lanes on consecutive entries, U of them in flight per lane.
+//   Qw[blk][j] = sum_{row in blk} X[row] * Phat_j[row]
+template <int RC>
+__global__ void __launch_bounds__(kRowThreads)
+vec_col_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
+               const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
+               float *const *__restrict__ xs, const float *__restrict__ phat,
+               double *__restrict__ qw) {
+    constexpr int U = 4;
+    const ColTile t = tiles[tile_index(ntiles, reverse)];
+    const PairDesc pd = pairs[t.pair];
+    const float *X = xs[pd.worker] + pd.x_off;
+    const int R = pd.R;
+    const int rb = t.blk * pd.blk_rows;
+    const int re = min(pd.p, rb + pd.blk_rows);
+    const float *ph[RC];
+    double acc[RC];
+#pragma unroll
+    for (int j = 0; j < RC; ++j) {
+        ph[j] = phat + cols[pd.col0 + min(j, R - 1)].ph_off;
+        acc[j] = 0.0;
+    }
+    for (int base = rb + (int)threadIdx.x; base < re; base += 64 * U) {
+        float x[U], f[U][RC];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int row = min(base + 64 * u, re - 1);
+            x[u] = ldg1(X + row);
+#pragma unroll
+            for (int j = 0; j < RC; ++j) f[u][j] = ldg1(ph[j] + row);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const double xd = base + 64 * u < re ? (double)x[u] : 0.0;
+#pragma unroll
+            for (int j = 0; j < RC; ++j) acc[j] = fma(xd, (double)f[u][j], acc[j]);
+        }
+    }
+    group_sum_all<RC>(acc, 64);
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int j = 0; j < RC; ++j)
+            if (j < R) qw[pd.qw_off + (int64_t)t.blk * R + j] = acc[j];
     }
 }
 

@@ -370,22 +370,31 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     // many stacked columns: one class (one kernel instantiation) per vector width
     // (tiles of different column groups of one matrix must not update it at the same time: every
     // group index has launches of its own)
-    auto row_class = [&](int RC, int V, bool mfma, int group) -> size_t {
+    auto row_class = [&](int RC, int V, bool mfma, int group, bool vec) -> size_t {
         if (RC < kWideCols) V = 0;
         for (size_t k = 0; k < P.row_classes.size(); ++k)
             if (P.row_classes[k].RC == RC && P.row_classes[k].V == V && P.row_classes[k].mfma == mfma &&
-                P.row_classes[k].group == group)
+                P.row_classes[k].group == group && P.row_classes[k].vec == vec)
                 return k;
-        P.row_classes.push_back({RC, V, mfma, {}, 0, 0, 0, group});
+        P.row_classes.push_back({RC, V, mfma, {}, 0, 0, 0, group, vec});
         return P.row_classes.size() - 1;
     };
-    auto col_class = [&](int RC, int V) -> size_t {
+    auto col_class = [&](int RC, int V, bool vec) -> size_t {
         if (RC < kWideCols) V = 0;
         for (size_t k = 0; k < P.col_classes.size(); ++k)
-            if (P.col_classes[k].RC == RC && P.col_classes[k].V == V) return k;
-        P.col_classes.push_back({RC, V, {}, 0, 0, 0});
+            if (P.col_classes[k].RC == RC && P.col_classes[k].V == V && P.col_classes[k].vec == vec) return k;
+        P.col_classes.push_back({RC, V, {}, 0, 0, 0, vec});
         return P.col_classes.size() - 1;
     };
+    // Vector layers (biases, normalisation scales) are a sliver of the bytes; as tiles of the matrix
+    // kernels they run at those kernels' low occupancy, one short latency-bound wavefront after the
+    // other.  Where there are many of them they get launches of their own with a kernel that needs
+    // few registers; where there are few, another launch would cost more than it saves.
+    int64_t vec_pairs = 0;
+    for (int l = 0; l < n_layers; ++l)
+        if (P.layers[l].q == 1)
+            for (int i = 0; i < n_workers; ++i) vec_pairs += P.pair_count[(size_t)l * n_workers + i];
+    const bool split_vec = tune.vec_kernels >= 2 || (tune.vec_kernels == 1 && vec_pairs >= kVecClassPairs);
     for (int l = 0; l < n_layers; ++l) {
         const LayerInfo &L = P.layers[l];
         const Geo &g = geo[l];
@@ -400,7 +409,8 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             }
             int RC = compiled_cols(pd.R);
             const bool mrow = g.mrow && RC >= kWideCols;
-            RowClass &rc = P.row_classes[row_class(RC, L.V, mrow, gi)];
+            const bool vec = split_vec && L.q == 1 && RC < kWideCols;
+            RowClass &rc = P.row_classes[row_class(RC, L.V, mrow, gi, vec)];
             int rows_iter = g.rows_iter_base * rows_unroll(RC);
             int tile_rows;
             if (RC < kWideCols) {
@@ -410,6 +420,9 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
                     iters = (int)std::max<int64_t>(1, tn.row_tile_bytes / bytes_iter);
                 }
                 tile_rows = rows_iter * iters;
+                // the vector kernel: one step (four entries per lane) per tile, so that a long vector
+                // is several short independent tiles and not one latency-bound loop
+                if (vec) tile_rows = 256;
             } else if (mrow) {
                 tile_rows = 16 * kMfmaRowBlocks * (4 / g.wc);
             } else {
@@ -425,7 +438,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             rc.elems += (double)L.p * L.q;
             P.pass_elems += (double)L.p * L.q;
 
-            ColClass &cc = P.col_classes[col_class(RC, L.V)];
+            ColClass &cc = P.col_classes[col_class(RC, L.V, vec)];
             int cw = (RC >= kWideCols && tune.mfma_cols) ? kMfmaTileCols : g.lg * L.V;
             for (int b = 0; b < g.nblk; ++b)
                 for (int c0 = 0; c0 < L.q; c0 += cw) cc.tiles.push_back({pair, c0, b, 0});

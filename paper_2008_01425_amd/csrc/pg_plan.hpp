@@ -29,6 +29,7 @@ struct RowClass {
     int max_seg = 0;        // RC >= kWideCols: longest column segment (sizes the Q slice in LDS)
     int group = 0;          // which of a worker's column groups these tiles belong to (0 unless a worker
                             // has more than kMaxCols stacked columns)
+    bool vec = false;       // vector layers (q = 1) only, run by the light-weight vector kernel
 };
 struct ColClass {
     int RC;
@@ -37,6 +38,7 @@ struct ColClass {
     size_t dev_first = 0;
     double elems = 0;
     int max_rows = 0;       // largest row block (sizes the staged Phat slice in LDS)
+    bool vec = false;       // as in RowClass
 };
 
 struct Tuning {
@@ -48,6 +50,8 @@ struct Tuning {
     bool mfma_cols = true;            // Q-sweep
     bool mfma_rows = true;            // P-sweep and update ...
     int mfma_row_cols = kMfmaRowCols; // ... of layers with at least this many stacked columns (8 or 16)
+    int vec_kernels = 1;              // vector layers in launches of their own (light-weight kernels):
+                                      // 0 never, 1 where there are many of them, 2 always
 };
 
 struct Plan {

@@ -60,6 +60,9 @@ static int check(const char *name, int n, const std::vector<int32_t> &e, const s
             REQUIRE(t.nrows >= 1 && t.row0 >= 0 && t.row0 + t.nrows <= pd.p, "row tile rows %d+%d of %d", t.row0, t.nrows, pd.p);
             REQUIRE(t.seg >= 0 && t.seg < pd.nseg && (int64_t)t.seg * pd.seg_len < pd.q, "segment %d", t.seg);
             if (c.RC >= kWideCols) REQUIRE(c.V == pd.V, "class V=%d, layer V=%d", c.V, pd.V);
+            if (c.vec) REQUIRE(pd.q == 1 && c.RC < kWideCols && t.nrows <= 256, "vector tile: q=%d, RC=%d, %d rows", pd.q, c.RC, t.nrows);
+            if (tune.vec_kernels == 2 && c.RC < kWideCols) REQUIRE(c.vec == (pd.q == 1), "vector layer outside the vector classes (q=%d)", pd.q);
+            if (tune.vec_kernels == 0) REQUIRE(!c.vec, "vector class although switched off");
             if (c.mfma) {
                 REQUIRE(pd.wc == 1 || pd.wc == 2 || pd.wc == 4, "wc=%d", pd.wc);
                 REQUIRE(pd.seg_len % 64 == 0, "seg_len=%d", pd.seg_len);
@@ -83,6 +86,8 @@ static int check(const char *name, int n, const std::vector<int32_t> &e, const s
             const PairDesc &pd = P.pairs[t.pair];
             REQUIRE(compiled_cols(pd.R) == c.RC, "pair %d with R=%d in column class RC=%d", t.pair, pd.R, c.RC);
             REQUIRE(t.blk >= 0 && t.blk < pd.nblk && (int64_t)t.blk * pd.blk_rows < pd.p, "row block %d", t.blk);
+            if (c.vec) REQUIRE(pd.q == 1 && c.RC < kWideCols, "vector column tile: q=%d, RC=%d", pd.q, c.RC);
+            if (tune.vec_kernels == 2 && c.RC < kWideCols) REQUIRE(c.vec == (pd.q == 1), "vector layer outside the vector column classes (q=%d)", pd.q);
             const int cw = (c.RC >= kWideCols && P.mfma_cols) ? kMfmaTileCols : pd.lg * pd.V;
             REQUIRE(t.c0 >= 0 && t.c0 < pd.q && t.c0 % cw == 0, "column tile at %d, width %d", t.c0, cw);
             if (!(c.RC >= kWideCols && P.mfma_cols)) {
@@ -147,10 +152,12 @@ static int check(const char *name, int n, const std::vector<int32_t> &e, const s
 
 int main() {
     int bad = 0;
-    std::vector<Tuning> tunings(3);
+    std::vector<Tuning> tunings(4);
     tunings[1].mfma_rows = false;
+    tunings[1].vec_kernels = 0;
     tunings[2].mfma_rows = false;
     tunings[2].mfma_cols = false;
+    tunings[3].vec_kernels = 2;
     for (const Tuning &tn : tunings) {
         std::vector<int32_t> e;
         ring(4, e);
@@ -227,7 +234,7 @@ int main() {
         }
         char label[64];
         snprintf(label, sizeof(label), "random %d", trial);
-        bad |= check(label, n, e, w, r, c, rnd(1, 16), rnd(1, 3), tunings[trial % 3]);
+        bad |= check(label, n, e, w, r, c, rnd(1, 16), rnd(1, 3), tunings[trial % tunings.size()]);
         ++nrandom;
     }
     if (!bad) printf("ok %d random problems\n", nrandom);

@@ -623,6 +623,30 @@ def test_sixteen_stacked_columns_on_the_vector_kernels():
                 os.environ[k] = v
 
 
+@pytest.mark.parametrize("mode", ["0", "2"])
+def test_vector_layers_with_and_without_kernels_of_their_own(mode):
+    """Vector layers (q = 1) run either as tiles of the matrix kernels or, where a parameter set
+    has many of them, in launches of their own; both ways against the oracle, on a ring (two
+    stacked columns), a torus (four) and with the gradient term, with vectors long enough for
+    several steps per lane and a ragged end."""
+    old = os.environ.get("PG_VEC_KERNELS")
+    os.environ["PG_VEC_KERNELS"] = mode
+    try:
+        shapes = [(700, 1), (64, 48), (2049, 1), (37, 1), (256, 1), (16, 130)]
+        wl = _custom("ring5_vectors", 5, W.ring_edges(5), 1 / 3, shapes, 2, 1)
+        _check(wl, 1, TOL_1)
+        _check(wl, 10, TOL_10, fused=True)
+        wl = _custom("torus3x3_vectors", 9, W.torus_edges(3, 3), 1 / 5, shapes, 1, 2)
+        _check(wl, 1, TOL_1)
+        _check(wl, 4, TOL_10, fused=True)
+        _check_sgd(wl, [0.1, 0.05], TOL_10)
+    finally:
+        if old is None:
+            os.environ.pop("PG_VEC_KERNELS", None)
+        else:
+            os.environ["PG_VEC_KERNELS"] = old
+
+
 @pytest.mark.parametrize("bad", [float("nan"), float("inf")])
 def test_non_finite_values_stay_in_their_layer(bad):
     """A NaN or an infinity in one worker's copy of one layer: the calls still succeed, the value

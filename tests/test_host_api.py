@@ -241,7 +241,7 @@ def test_planner_tiles_cover_every_matrix_exactly_once(tmp_path):
     assert build.returncode == 0, build.stderr[-3000:]
     run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
     assert run.returncode == 0, run.stdout[-3000:]
-    assert run.stdout.count("ok ") == 34 and "FAIL" not in run.stdout
+    assert run.stdout.count("ok ") == 45 and "FAIL" not in run.stdout
 
 
 SAN = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-g"]
@@ -266,7 +266,7 @@ def test_planner_under_address_and_undefined_behaviour_sanitizers(tmp_path):
     src = [os.path.join(ROOT, "tests", "plan_cover.cpp"),
            os.path.join(ROOT, "paper_2008_01425_amd", "csrc", "pg_plan.cpp")]
     out = _run_sanitized(["g++", "-O1", "-std=c++17"] + SAN + ["-o", exe] + src, exe)
-    assert "FAIL" not in out and out.count("ok ") == 34
+    assert "FAIL" not in out and out.count("ok ") == 45
 
 
 @pytest.mark.parametrize("define", [[], ["-DPGO_ALL_DOUBLE"]])

@@ -640,6 +640,8 @@ def test_vector_layers_with_and_without_kernels_of_their_own(mode):
         _check(wl, 1, TOL_1)
         _check(wl, 4, TOL_10, fused=True)
         _check_sgd(wl, [0.1, 0.05], TOL_10)
+        wl = _custom("torus3x3_vectors_iter", 9, W.torus_edges(3, 3), 1 / 5, shapes, 1, 1)
+        _check_iterate(wl, [1, 1, 2], TOL_10, eta=0.05)
     finally:
         if old is None:
             os.environ.pop("PG_VEC_KERNELS", None)

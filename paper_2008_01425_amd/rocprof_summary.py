@@ -55,13 +55,13 @@ def pmc_stats(path: str) -> str:
 
 def kernel_kind(name: str):
     """Kernel name -> the kind pg_profile_collect reports it under (None: not a pass over X)."""
-    m = re.match(r"pg::(row_kernel|row_wide_kernel|mrow_kernel)<(.*)>", name)
+    m = re.match(r"pg::(row_kernel|row_wide_kernel|mrow_kernel|vec_row_kernel)<(.*)>", name)
     if m:
         upd, swp, grad = [t.strip() == "true" for t in m.group(2).split(",")[-3:]]
         if grad:
             return "update_sgd"
         return "update_sweep_p" if upd and swp else ("update" if upd else "sweep_p")
-    if re.match(r"pg::(col_kernel|mcol_kernel)<", name):
+    if re.match(r"pg::(col_kernel|mcol_kernel|vec_col_kernel)<", name):
         return "sweep_q"
     return None
 

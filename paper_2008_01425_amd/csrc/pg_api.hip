@@ -136,6 +136,7 @@ int do_upload(pg_ctx *c) {
 // step ahead beat fewer rows with a deeper pipeline for every mode and column count, also where
 // part of the M * RC accumulators and update coefficients then lives in accumulation registers.
 constexpr int kRowsPerGroup = 8;
+constexpr int kRowsPerGroupLight = 4;  // small parameter sets (Plan::light)
 constexpr int kPrefetchSteps = 1;
 // Matrix-core kernels: steps a row tile and a column tile load ahead (measured on the
 // LSTM-shaped torus: deeper rings only cost registers).
@@ -198,6 +199,9 @@ struct Launcher {
         if constexpr (RC < kWideCols) {
             if (rc.vec)
                 vec_row_kernel<RC, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
+                    tiles, n, c->reverse, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
+            else if (c->plan.light)
+                row_kernel<RC, kRowsPerGroupLight, kPrefetchSteps, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
                     tiles, n, c->reverse, c->d_pairs, c->d_cols, c->d_xs, right(), left(), pw(), c->d_gs, eta);
             else
                 row_kernel<RC, kRowsPerGroup, kPrefetchSteps, UPD, SWP, GRAD><<<dim3((unsigned)n), dim3(kRowThreads), 0, st>>>(
@@ -493,6 +497,7 @@ int pg_init(pg_ctx **out, int n_workers, int n_edges, const int32_t *edges, cons
     if (const char *e = getenv("PG_MCOL_TILE_BYTES")) tune.mcol_tile_bytes = std::max(1024, atoi(e));
     if (const char *e = getenv("PG_MFMA_ROWS")) tune.mfma_rows = atoi(e) != 0;
     if (const char *e = getenv("PG_MFMA_COLS")) tune.mfma_cols = atoi(e) != 0;
+    if (const char *e = getenv("PG_LIGHT")) tune.light = atoi(e) != 0;
     if (const char *e = getenv("PG_VEC_KERNELS")) tune.vec_kernels = std::min(2, std::max(0, atoi(e)));
     if (const char *e = getenv("PG_MFMA_ROW_COLS")) tune.mfma_row_cols = atoi(e) <= 8 ? 8 : 16;
     int rc;

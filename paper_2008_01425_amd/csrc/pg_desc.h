@@ -12,6 +12,7 @@ namespace pg {
 constexpr int kMaxCols = 16;   // largest R = deg(i) * r_l one pass supports
 constexpr int kThreads = 256;  // work-group size of the column-owner and combine kernels (4 wavefronts)
 constexpr int kRowThreads = 64;  // narrow row-owner kernels: one wavefront per tile
+constexpr int64_t kLightBytes = 64ll << 20;  // parameter bytes (all workers) up to which the narrow row kernels block 4 rows, not 8
 constexpr int kVecClassPairs = 1024;  // (worker, vector layer) pairs from which vector layers get kernels of their own
 constexpr int kWideCols = 8;     // from this many compiled columns on, row tiles stage Q in LDS
 constexpr int kWideLdsBytes = 48 * 1024;  // LDS budget of a wide row tile's Q slice

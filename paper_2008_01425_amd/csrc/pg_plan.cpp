@@ -22,8 +22,8 @@ int compiled_cols(int R) {
     return rc;
 }
 
-int rows_unroll(int RC) {
-    if (RC < kWideCols) return 8;
+int rows_unroll(int RC, bool light) {
+    if (RC < kWideCols) return light ? 4 : 8;
     return 4;
 }
 
@@ -123,7 +123,8 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
     {
         const double total_bytes = 4.0 * n_workers * P.elems_per_worker;
         const double slots = 4096.0;  // 256 CUs x 4 SIMDs x a few wavefronts
-        tn.row_tile_bytes = (int)std::max(8.0 * 1024, std::min((double)tune.row_tile_bytes, total_bytes / slots));
+        P.light = tune.light < 0 ? total_bytes <= (double)kLightBytes : tune.light != 0;
+        tn.row_tile_bytes = (int)std::max((P.light ? 4.0 : 8.0) * 1024, std::min((double)tune.row_tile_bytes, total_bytes / slots));
         tn.col_tile_bytes = (int)std::max(32.0 * 1024, std::min((double)tune.col_tile_bytes, 4.0 * total_bytes / slots));
         tn.wide_tile_bytes = (int)std::max(32.0 * 1024, std::min((double)tune.wide_tile_bytes, 4.0 * total_bytes / slots));
         tn.mcol_tile_bytes = (int)std::max(64.0 * 1024, std::min((double)tune.mcol_tile_bytes, 8.0 * total_bytes / slots));
@@ -160,7 +161,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
         if (!g.wide) {
             // one wavefront per tile: column segments keep a tile near the byte target when a
             // single row is long
-            int rows_iter = (64 / g.lpr) * rows_unroll(rc_max);
+            int rows_iter = (64 / g.lpr) * rows_unroll(rc_max, P.light);
             int64_t chunk_bytes = (int64_t)rows_iter * chunk * 4;
             seg_chunks = (int)std::max<int64_t>(1, tn.row_tile_bytes / chunk_bytes);
             g.rows_iter_base = 64 / g.lpr;
@@ -411,7 +412,7 @@ int build_plan(Plan &P, int n_workers, int n_edges, const int32_t *edges, const 
             const bool mrow = g.mrow && RC >= kWideCols;
             const bool vec = split_vec && L.q == 1 && RC < kWideCols;
             RowClass &rc = P.row_classes[row_class(RC, L.V, mrow, gi, vec)];
-            int rows_iter = g.rows_iter_base * rows_unroll(RC);
+            int rows_iter = g.rows_iter_base * rows_unroll(RC, P.light);
             int tile_rows;
             if (RC < kWideCols) {
                 int iters = 1;

@@ -50,6 +50,7 @@ struct Tuning {
     bool mfma_cols = true;            // Q-sweep
     bool mfma_rows = true;            // P-sweep and update ...
     int mfma_row_cols = kMfmaRowCols; // ... of layers with at least this many stacked columns (8 or 16)
+    int light = -1;                   // blocking for small parameter sets: -1 by size, 0 never, 1 always
     int vec_kernels = 1;              // vector layers in launches of their own (light-weight kernels):
                                       // 0 never, 1 where there are many of them, 2 always
 };
@@ -84,12 +85,18 @@ struct Plan {
     std::vector<OrthTile> orth_tiles;        // filled only when some layer has more than one row chunk
     std::vector<RowClass> row_classes;
     std::vector<ColClass> col_classes;
+    // A small parameter set (all workers together at most kLightBytes) does not fill the chip with
+    // the tiles that serve a large one: a pass is then as long as one wavefront's chain of
+    // dependent loads, so the narrow row kernels block fewer rows per lane group (half the
+    // registers, twice the wavefronts per SIMD) over tiles half as large.
+    bool light = false;
     int max_layer_rank = 1;                  // largest r_l
     int max_rows = 1;                        // largest p_l
 };
 
-// Rows one work-group covers per pass for a compiled column count (register blocking).
-int rows_unroll(int RC);
+// Rows one lane group covers per step for a compiled column count (register blocking); `light`:
+// the blocking for small parameter sets (see Plan::light).
+int rows_unroll(int RC, bool light = false);
 // Smallest compiled column count >= R (1, 2, 4, 8, 16).
 int compiled_cols(int R);
 

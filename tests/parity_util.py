@@ -1,5 +1,6 @@
 """Shared helpers of the GPU parity tests: run the HIP path and the CPU oracle on the same
 seeded inputs and compare element by element."""
+import contextlib
 import copy
 import os
 from concurrent.futures import ThreadPoolExecutor
@@ -10,6 +11,20 @@ from oracle import pg_oracle as O
 
 TOL_1 = 1e-5     # relative error per element after one round
 TOL_10 = 1e-4    # after ten rounds
+
+
+@contextlib.contextmanager
+def env_setting(name, value):
+    """Set an environment variable the library reads in pg_init for the duration of the block."""
+    old = os.environ.get(name)
+    os.environ[name] = str(value)
+    try:
+        yield
+    finally:
+        if old is None:
+            os.environ.pop(name, None)
+        else:
+            os.environ[name] = old
 
 
 def rel_err(got: np.ndarray, ref: np.ndarray) -> float:

@@ -187,7 +187,9 @@ int pg_round_static(pg_ctx *ctx, float *const *worker_params, float *q_state, vo
  * SGD step).  Both terms enter one double-precision sum that is rounded to float once.
  *   worker_grads   host array of n_workers DEVICE pointers, laid out like the parameter
  *                  buffers (pg_param_floats floats, same layer offsets), 16-byte aligned;
- *                  read only.  Cached like worker_params.
+ *                  read only.  Cached like worker_params.  Any update direction may stand
+ *                  here: with momentum (the Cifar-10 settings of the appendix use 0.9) the
+ *                  caller keeps the momentum buffer and passes it as G.
  *   eta            learning rate (finite, else PG_ERR_ARG)
  * Workers without edges get X_i -= eta * G_i.  Other arguments and errors as pg_round.
  */

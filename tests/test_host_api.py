@@ -276,3 +276,24 @@ def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path, defin
     src = os.path.join(ROOT, "tests", "oracle_sanitize.c")
     out = _run_sanitized(["gcc", "-O1", "-std=c11", "-ffp-contract=off"] + SAN + define + ["-o", exe, src, "-lm"], exe)
     assert "oracle sanitize ok" in out
+
+
+def test_profile_summaries_classify_every_pass_kernel():
+    """The rocprofv3 summariser maps kernel names to the kinds pg_profile_collect reports; the
+    committed traffic summaries are read back by bench.py under those kinds."""
+    from paper_2008_01425_amd.rocprof_summary import kernel_kind
+    assert kernel_kind("pg::row_kernel<2, 8, 1, true, true, false>") == "update_sweep_p"
+    assert kernel_kind("pg::row_kernel<2, 4, 1, false, true, false>") == "sweep_p"
+    assert kernel_kind("pg::row_wide_kernel<4, 8, 4, true, false, false>") == "update"
+    assert kernel_kind("pg::mrow_kernel<2, 4, 2, 1, true, false, true>") == "update_sgd"
+    assert kernel_kind("pg::vec_row_kernel<4, true, true, false>") == "update_sweep_p"
+    assert kernel_kind("pg::vec_row_kernel<4, false, true, false>") == "sweep_p"
+    assert kernel_kind("pg::col_kernel<0, 2, 8>") == "sweep_q"
+    assert kernel_kind("pg::mcol_kernel<4, 2>") == "sweep_q"
+    assert kernel_kind("pg::vec_col_kernel<4>") == "sweep_q"
+    assert kernel_kind("pg::comb_kernel") is None
+    assert kernel_kind("pg::orth_gram_kernel<256, 2>") is None
+    for wl in ("vgg16_r1", "vgg16_r2", "lstm", "resnet50"):
+        path = os.path.join(ROOT, "profiles", f"{wl}_traffic_counters.txt")
+        kinds = {line.split()[1] for line in open(path) if line.startswith("traffic ")}
+        assert kinds == {"sweep_p", "sweep_q", "update", "update_sweep_p"}, (wl, kinds)

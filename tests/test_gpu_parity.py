@@ -632,7 +632,7 @@ def test_vector_layers_with_and_without_kernels_of_their_own(mode):
     old = os.environ.get("PG_VEC_KERNELS")
     os.environ["PG_VEC_KERNELS"] = mode
     try:
-        shapes = [(700, 1), (64, 48), (2049, 1), (37, 1), (256, 1), (16, 130)]
+        shapes = [(700, 1), (64, 48), (2049, 1), (37, 1), (20001, 1), (256, 1), (16, 130)]
         wl = _custom("ring5_vectors", 5, W.ring_edges(5), 1 / 3, shapes, 2, 1)
         _check(wl, 1, TOL_1)
         _check(wl, 10, TOL_10, fused=True)

@@ -342,9 +342,9 @@ struct Launcher {
                 c->d_els, pw(), ph(), flags());
         } else {
             dim3 grid((unsigned)P.orth_tiles.size());
-            orth_gram_part_kernel<NT, RMAX><<<grid, dim3(NT), 0, st>>>(c->d_orth, c->d_els, pw(), gpart());
+            orth_gram_part_kernel<NT, RMAX><<<grid, dim3(NT), 0, st>>>(c->d_orth, c->d_els, pw(), gpart(), nullptr);
             orth_gram_apply_kernel<NT, RMAX><<<grid, dim3(NT), 0, st>>>(c->d_orth, c->d_els, pw(), gpart(),
-                                                                        ph(), flags());
+                                                                        ph(), flags(), nullptr);
         }
     }
     void orth_p() {
@@ -366,8 +366,18 @@ struct Launcher {
     // Algorithm 2's normalisation of the stored vectors (Gram-Schmidt for r > 1): src -> dst.
     template <int RMAX>
     void orth_v_launch(const float *src, float *dst, int in_q) {
+        const Plan &P = c->plan;
+        if (!in_q && !P.orth_tiles.empty()) {
+            // vectors of length p with tall layers among them: chunk by chunk, like the round's own
+            // orthonormalisation
+            dim3 grid((unsigned)P.orth_tiles.size());
+            orth_gram_part_kernel<256, RMAX><<<grid, dim3(256), 0, st>>>(c->d_orth, c->d_els, nullptr, gpart(), src);
+            orth_gram_apply_kernel<256, RMAX><<<grid, dim3(256), 0, st>>>(c->d_orth, c->d_els, nullptr, gpart(),
+                                                                          dst, flags(), src);
+            return;
+        }
         constexpr int NT = RMAX <= 4 ? 1024 : 512;
-        orth_state_kernel<NT, RMAX><<<dim3((unsigned)c->plan.els.size()), dim3(NT), 0, st>>>(
+        orth_state_kernel<NT, RMAX><<<dim3((unsigned)P.els.size()), dim3(NT), 0, st>>>(
             c->d_els, src, dst, in_q, flags());
     }
     void orth_v(const float *src, float *dst, int in_q) {
@@ -385,7 +395,11 @@ struct Launcher {
     void combine_p(float *pstate) {
         if (status || c->plan.els.empty()) return;
         begin(K_COMBINE_P, 0.0);
-        comb_p_kernel<<<dim3((unsigned)c->plan.els.size()), dim3(kThreads), 0, st>>>(c->d_els, pw(), flags(), pstate);
+        // a grid's second dimension holds at most 65535 chunks
+        const int chunk_rows = std::max(kCombPRows, (c->plan.max_rows + 65534) / 65535);
+        const unsigned chunks = (unsigned)((c->plan.max_rows + chunk_rows - 1) / chunk_rows);
+        comb_p_kernel<<<dim3((unsigned)c->plan.els.size(), chunks), dim3(kThreads), 0, st>>>(c->d_els, pw(), flags(), pstate,
+                                                                                             chunk_rows);
         check();
         end();
     }

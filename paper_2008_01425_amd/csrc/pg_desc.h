@@ -79,6 +79,7 @@ struct OrthTile {
     int32_t el, row0, nrows, chunk, nchunks, pad;
 };
 constexpr int kOrthTallRows = 4096;   // layers taller than this are orthonormalised chunk by chunk
+constexpr int kCombPRows = 2048;      // rows per work-group of the p-side combine of single iterations
 constexpr int kOrthChunkRows = 1024;  // rows per chunk (one work-group of 256 threads)
 
 // combine_q tile: 256 consecutive elements of the r*q block of one (edge, layer).

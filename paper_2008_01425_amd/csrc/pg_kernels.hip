@@ -1460,13 +1460,18 @@ orth_state_kernel(const EdgeLayerDesc *__restrict__ els, const float *__restrict
 // Algorithm 2, odd iteration: v_ij <- p_j - p_i, the difference of the two workers' products,
 // stored unnormalised as float columns of length p; columns whose unit vector was dropped keep
 // their old content.
+// Grid: (edge, layer) x chunks of chunk_rows rows (sized for the tallest layer; chunks past a
+// layer's end leave at once).
 __global__ void __launch_bounds__(kThreads)
 comb_p_kernel(const EdgeLayerDesc *__restrict__ els, const double *__restrict__ pw,
-              const int32_t *__restrict__ flags, float *__restrict__ pstate) {
+              const int32_t *__restrict__ flags, float *__restrict__ pstate, int chunk_rows) {
     const EdgeLayerDesc d = els[blockIdx.x];
+    const int64_t first = (int64_t)blockIdx.y * chunk_rows;
+    const int row0 = (int)min<int64_t>(first, d.p);
+    const int row1 = (int)min<int64_t>(first + chunk_rows, d.p);
     for (int k = 0; k < d.r; ++k) {
-        if (flags[d.flag_off + k]) continue;
-        for (int row = threadIdx.x; row < d.p; row += kThreads) {
+        if (row0 >= row1 || flags[d.flag_off + k]) continue;
+        for (int row = row0 + (int)threadIdx.x; row < row1; row += kThreads) {
             double sa = 0.0, sb = 0.0;
             for (int s = 0; s < d.nseg; ++s) {
                 sa += pw[d.pwa_off + s * d.pwa_seg + (int64_t)k * d.p + row];
@@ -1483,13 +1488,16 @@ comb_p_kernel(const EdgeLayerDesc *__restrict__ els, const double *__restrict__ 
 template <int NT, int RMAX>
 __global__ void __launch_bounds__(NT)
 orth_gram_part_kernel(const OrthTile *__restrict__ tiles, const EdgeLayerDesc *__restrict__ els,
-                      const double *__restrict__ pw, double *__restrict__ gpart) {
+                      const double *__restrict__ pw, double *__restrict__ gpart,
+                      const float *__restrict__ st) {
     constexpr int NG = RMAX * (RMAX + 1) / 2;
     __shared__ double sRed[NT / 64][NG];
     __shared__ double sG[NG];
     const OrthTile t = tiles[blockIdx.x];
     const EdgeLayerDesc d = els[t.el];
-    const GramIO io{pw, nullptr, 0, d.p, nullptr, 0};
+    // st: the stored float columns of length p to normalise (Algorithm 2's vectors) instead of
+    // the difference of the partial products
+    const GramIO io{pw, st, d.ph_off, d.p, nullptr, 0};
     gram_rows<NT, RMAX>(d, io, t.row0, t.row0 + t.nrows, sRed, sG);
     if (threadIdx.x < NG) gpart[(int64_t)blockIdx.x * NG + threadIdx.x] = sG[threadIdx.x];
 }
@@ -1498,7 +1506,8 @@ template <int NT, int RMAX>
 __global__ void __launch_bounds__(NT)
 orth_gram_apply_kernel(const OrthTile *__restrict__ tiles, const EdgeLayerDesc *__restrict__ els,
                        const double *__restrict__ pw, const double *__restrict__ gpart,
-                       float *__restrict__ phat, int32_t *__restrict__ flags) {
+                       float *__restrict__ phat, int32_t *__restrict__ flags,
+                       const float *__restrict__ st) {
     constexpr int NG = RMAX * (RMAX + 1) / 2;
     __shared__ double sG[NG];
     __shared__ double sR[RMAX][RMAX];
@@ -1513,7 +1522,7 @@ orth_gram_apply_kernel(const OrthTile *__restrict__ tiles, const EdgeLayerDesc *
     }
     __syncthreads();
     gram_factor<RMAX>(d, sG, sR, sDrop, flags, t.chunk == 0);
-    const GramIO io{pw, nullptr, 0, d.p, phat, d.ph_off};
+    const GramIO io{pw, st, d.ph_off, d.p, phat, d.ph_off};
     gram_apply_rows<NT, RMAX>(d, io, t.row0, t.row0 + t.nrows, sR, sDrop);
 }
 

@@ -161,6 +161,9 @@ def test_tall_embedding_shaped_layer():
     wl = _custom("tall_embedding", 3, W.ring_edges(3), 1 / 3, [(33278, 650)], 2, 2, sigma=0.01)
     _check(wl, 1, TOL_1)
     _check(wl, 2, TOL_10, fused=True)
+    # single iterations: the vectors in R^p are normalised and combined chunk by chunk as well
+    wl = _custom("tall_embedding_iter", 3, W.ring_edges(3), 1 / 3, [(33278, 650), (5000, 1), (40, 30)], 2, 1, sigma=0.01)
+    _check_iterate(wl, [1, 1, 1, 1], TOL_10, eta=0.05)
 
 
 def test_random_projections_fresh_state_every_round():

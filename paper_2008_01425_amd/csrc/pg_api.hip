@@ -56,6 +56,7 @@ struct pg_ctx {
     std::vector<float *> xs_cached;
     float **d_gs = nullptr;
     std::vector<const float *> gs_cached;
+    bool mcol_stage = true;  // matrix-core Q-sweep: Phat of a tile's row block staged in LDS
     bool profiling = false;
     // Passes alternate direction through the parameters: each starts where the one before it
     // (also the last one of an earlier call) ended, on data still in the memory-side cache.
@@ -301,12 +302,22 @@ struct Launcher {
             else
                 PG_COL(0);
         } else if (c->plan.mfma_cols) {
-#define PG_MCOL(VV) mcol_kernel<VV, kMfmaColPrefetch><<<dim3((unsigned)n), dim3(kThreads), 0, st>>>( \
+#define PG_MCOL(VV, STAGE, LDS) mcol_kernel<VV, kMfmaColPrefetch, STAGE><<<dim3((unsigned)n), dim3(kThreads), LDS, st>>>( \
             c->d_col_tiles + cc.dev_first, n, c->reverse, c->d_pairs, c->d_cols, \
             c->d_xs, left(), qw())
-            if (cc.V == 4) PG_MCOL(4);
-            else if (cc.V == 2) PG_MCOL(2);
-            else PG_MCOL(1);
+            // The row block's Phat slice in LDS, where it fits beside a second work-group's.  Measured:
+            // with 16 stacked columns the Q-sweep of the LSTM-shaped torus gains 5 % (430 -> 410 us);
+            // with 8 (half of the staged slice zeros, many short layers) it loses 0.5 %.
+            const size_t stage = (size_t)16 * mcol_stage_stride(cc.max_rows) * sizeof(float);
+            if (c->mcol_stage && RC >= 16 && stage <= 64 * 1024) {
+                if (cc.V == 4) PG_MCOL(4, true, stage);
+                else if (cc.V == 2) PG_MCOL(2, true, stage);
+                else PG_MCOL(1, true, stage);
+            } else {
+                if (cc.V == 4) PG_MCOL(4, false, 0);
+                else if (cc.V == 2) PG_MCOL(2, false, 0);
+                else PG_MCOL(1, false, 0);
+            }
 #undef PG_MCOL
         } else {
             if (cc.V == 4) PG_COL(4);
@@ -511,6 +522,7 @@ int pg_init(pg_ctx **out, int n_workers, int n_edges, const int32_t *edges, cons
     if (const char *e = getenv("PG_MCOL_TILE_BYTES")) tune.mcol_tile_bytes = std::max(1024, atoi(e));
     if (const char *e = getenv("PG_MFMA_ROWS")) tune.mfma_rows = atoi(e) != 0;
     if (const char *e = getenv("PG_MFMA_COLS")) tune.mfma_cols = atoi(e) != 0;
+    if (const char *e = getenv("PG_MCOL_STAGE")) c->mcol_stage = atoi(e) != 0;
     if (const char *e = getenv("PG_LIGHT")) tune.light = atoi(e) != 0;
     if (const char *e = getenv("PG_VEC_KERNELS")) tune.vec_kernels = std::min(2, std::max(0, atoi(e)));
     if (const char *e = getenv("PG_MFMA_ROW_COLS")) tune.mfma_row_cols = atoi(e) <= 8 ? 8 : 16;

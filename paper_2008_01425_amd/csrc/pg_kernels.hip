@@ -915,27 +915,44 @@ mrow_kernel(const RowTile *__restrict__ tiles, int ntiles, int reverse, const Pa
 // 16 V (v / V).  The instruction for (u, v) adds X^T Phat over the rows r + 4 hi + u, hi = 0..3:
 // D_v[col][j] += X[row][col] * Phat_j[row] (A = X^T, B = the stacked Phat columns, j = lo); a
 // lane's four Phat values of a step are consecutive in memory and come in one load.
-template <int V, int D>
+// STAGE: the row block's Phat entries, all 16 stacked columns, are staged in LDS once per tile
+// ([j][row], rows past the block's end and columns j >= R as zeros) and the four wavefronts take
+// their B operands from there; otherwise every wavefront fetches them from global memory step by step.
+__host__ __device__ constexpr int mcol_stage_stride(int blk_rows) { return ((blk_rows + 31) & ~31) + 4; }
+template <int V, int D, bool STAGE>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
 mcol_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
             const PairDesc *__restrict__ pairs, const ColDesc *__restrict__ cols,
             float *const *__restrict__ xs, const float *__restrict__ phat,
             double *__restrict__ qw) {
+    extern __shared__ double smem[];
+    float *sP = reinterpret_cast<float *>(smem);
     const ColTile t = tiles[tile_index(ntiles, reverse)];
     const PairDesc pd = pairs[t.pair];
     const float *X = xs[pd.worker] + pd.x_off;
     const int lane = threadIdx.x & 63, lo = lane & 15, hi = lane >> 4;
     const int q = pd.q, R = pd.R;
     const int c0 = t.c0 + 64 * __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    if (c0 >= q) return;
-    const int ncols = min(64, q - c0);  // this wavefront's columns inside the matrix
+    const bool mine = c0 < q;  // a wavefront past the matrix's last column only helps staging
+    if (!STAGE && !mine) return;
+    const int ncols = mine ? min(64, q - c0) : V;  // this wavefront's columns inside the matrix
     const int rb = t.blk * pd.blk_rows;
     const int re = min(pd.p, rb + pd.blk_rows);
     const int nsteps = (re - rb + 15) >> 4;
     const bool ragged = ((re - rb) & 15) != 0;
     const float *ph = phat + cols[pd.col0 + min(lo, R - 1)].ph_off;
     const bool jok = lo < R;
-    const float *xt = X + c0;
+    const float *xt = X + (mine ? c0 : 0);
+    const int stride = mcol_stage_stride(pd.blk_rows);
+    if (STAGE) {
+        const float *src[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) src[j] = phat + cols[pd.col0 + min(j, R - 1)].ph_off + rb;
+        for (int r = threadIdx.x; r < 16 * nsteps; r += kThreads) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) sP[j * stride + r] = (j < R && r < re - rb) ? ldg1(src[j] + r) : 0.0f;
+        }
+    }
 
     mfma_acc acc[4];
 #pragma unroll
@@ -948,11 +965,11 @@ mcol_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
     auto load = [&](int s, Buf &f) {
         const int r0 = rb + 16 * s + 4 * hi;
         const bool last = ragged && s == nsteps - 1;
-        if (!last) ld4(ph + r0, f.t);
+        if (!STAGE && !last) ld4(ph + r0, f.t);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int r = last ? min(r0 + u, re - 1) : r0 + u;
-            if (last) f.t[u] = ldg1(ph + r);
+            if (!STAGE && last) f.t[u] = ldg1(ph + r);
             const float *xr = xt + (int64_t)r * pd.ld;
 #pragma unroll
             for (int w = 0; w < 4 / V; ++w) {
@@ -967,9 +984,14 @@ mcol_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
     };
     auto process = [&](int s, Buf &f) {
         const int r0 = rb + 16 * s + 4 * hi;
+        if (STAGE) {
+            const VecT<4>::T tv = *reinterpret_cast<const VecT<4>::T *>(sP + lo * stride + 16 * s + 4 * hi);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) f.t[u] = tv[u];
+        }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const double td = (jok && r0 + u < re) ? (double)f.t[u] : 0.0;
+            const double td = (STAGE || (jok && r0 + u < re)) ? (double)f.t[u] : 0.0;
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[v] = mfma16((double)f.x[u][v], td, acc[v]);
         }
@@ -977,9 +999,15 @@ mcol_kernel(const ColTile *__restrict__ tiles, int ntiles, int reverse,
 
     constexpr int NB = D + 1;
     Buf ring[NB];
+    if (mine) {
 #pragma unroll
-    for (int k = 0; k < D; ++k)
-        if (k < nsteps) load(k, ring[k]);
+        for (int k = 0; k < D; ++k)
+            if (k < nsteps) load(k, ring[k]);
+    }
+    if (STAGE) {
+        __syncthreads();  // Phat staged (the first loads of X are already under way)
+        if (!mine) return;
+    }
     int s = 0;
     for (; s + NB + D <= nsteps; s += NB) {
 #pragma unroll
